@@ -728,7 +728,9 @@ int ggnn_ref_sym(ggnn_ref_graph* g, int layer, const ggnn_ref_build_params* p) {
       cache_release(&c);
     }
     /* grant the requested links */
-    int32_t* hold = (int32_t*)malloc(sizeof(int32_t) * (size_t)n * ksym); /* request index = z */
+    /* one spare slot per row: a newcomer is stored before the worst holder is evicted */
+    const int hs = ksym + 1;
+    int32_t* hold = (int32_t*)malloc(sizeof(int32_t) * (size_t)n * hs); /* request index = z */
     int32_t* nhold = (int32_t*)calloc((size_t)n, sizeof(int32_t));
     int64_t* queue = (int64_t*)malloc(sizeof(int64_t) * (size_t)(n + 1));
     int64_t qh = 0, qt = 0, qcap = n + 1;
@@ -746,7 +748,7 @@ int ggnn_ref_sym(ggnn_ref_graph* g, int layer, const ggnn_ref_build_params* p) {
       if (R->ptr >= R->npref) continue; /* no candidate with free capacity: link dropped */
       int32_t cand = R->pref[R->ptr].id;
       int cap = ksym - ninv[cand];
-      int32_t* H = hold + (int64_t)cand * ksym;
+      int32_t* H = hold + (int64_t)cand * hs;
       H[nhold[cand]++] = (int32_t)r;
       if (nhold[cand] > cap) {
         /* evict the holder with the largest (distance to its own midpoint, z) */
@@ -764,7 +766,7 @@ int ggnn_ref_sym(ggnn_ref_graph* g, int layer, const ggnn_ref_build_params* p) {
       }
     }
     for (int64_t c2 = 0; c2 < n; c2++) {
-      int32_t* H = hold + c2 * ksym;
+      int32_t* H = hold + c2 * hs;
       /* append the granted links in ascending (distance, z) */
       for (int i = 1; i < nhold[c2]; i++) {
         int32_t h = H[i]; int j = i;

@@ -137,9 +137,12 @@ class Graph:
         self.n = [lib().ggnn_ref_graph_n(self.h, l) for l in range(levels)]
 
     def __del__(self):
-        if getattr(self, "h", None):
-            lib().ggnn_ref_graph_free(self.h)
-            self.h = None
+        try:
+            if getattr(self, "h", None) and _lib is not None:
+                _lib.ggnn_ref_graph_free(self.h)
+                self.h = None
+        except Exception:  # interpreter shutdown
+            pass
 
     def _arr(self, fn, layer, shape):
         p = fn(self.h, layer)
