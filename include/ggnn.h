@@ -1,0 +1,163 @@
+/*
+ * ggnn.h -- C ABI of the MI355X (gfx950) implementation of GGNN's hot path:
+ * batched best-first search with a slack stopping rule over a hierarchical,
+ * fixed-out-degree kNN graph, and the bottom-up graph construction that is driven
+ * by the same search (Groh et al., "GGNN: Graph-based GPU Nearest Neighbor Search",
+ * arxiv 1912.01059).
+ *
+ * Conventions
+ *  - Every function returns 0 on success or a negative ggnn_status; it never aborts.
+ *    ggnn_last_error() returns a thread-local description of the last failure.
+ *  - Pointers named *_dev are device (HBM) pointers owned by the caller; pointers named
+ *    *_host are host pointers owned by the caller.  The library never frees them.
+ *  - Vectors are row-major, D elements per row, rows 16-byte aligned (D*sizeof(element)
+ *    must be a multiple of 16).  Ids are int32; byte offsets are 64-bit.
+ *  - `base_dev` is BORROWED by the graph and must outlive it (it is not copied, except
+ *    that a cosine graph owns a unit-length float32 copy).
+ *  - All work is issued on the stream given at creation (or per call for queries); calls
+ *    return after the work has completed unless stated otherwise.
+ *  - Distances are plain (not squared) Euclidean norms, or 1 - cos for GGNN_COSINE, in
+ *    float32.  Every ordered result uses the total order (distance, id).
+ *  - float32 sums follow one fixed order, so results are reproducible bit for bit: the
+ *    row is cut into 16-byte chunks, chunk c belongs to lane c mod GGNN_ROW_LANES, a lane
+ *    accumulates acc = fma(t, t, acc) over its chunks in ascending order, and the lanes
+ *    are combined by a butterfly (distance 4, 2, 1).
+ */
+#ifndef GGNN_H
+#define GGNN_H
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define GGNN_MAX_LEVELS 8
+#define GGNN_ROW_LANES 8
+
+typedef struct ggnn_graph ggnn_graph; /* opaque, owned by the library */
+
+typedef enum { GGNN_L2 = 0, GGNN_COSINE = 1 } ggnn_metric;
+typedef enum { GGNN_F32 = 0, GGNN_U8 = 1 } ggnn_dtype;
+
+typedef enum {
+  GGNN_OK = 0,
+  GGNN_ERR_INVALID = -1, /* bad argument (null pointer, size out of range, ...) */
+  GGNN_ERR_MEMORY = -2,  /* device or host allocation failed                    */
+  GGNN_ERR_HIP = -3,     /* a HIP runtime call or kernel launch failed          */
+  GGNN_ERR_LIMIT = -4    /* a capacity exceeds what one workgroup's LDS holds   */
+} ggnn_status;
+
+/* Construction parameters (appendix "Choosing Search-Graph Construction Parameters").
+ * A zero field selects the default given in brackets. */
+typedef struct {
+  int32_t metric;         /* ggnn_metric [GGNN_L2]                                     */
+  int32_t dtype;          /* ggnn_dtype of base and queries [GGNN_F32]                 */
+  int32_t segment_size;   /* s: points per segment and per top layer [32], <= 64       */
+  float tau_build;        /* slack factor tau_b of the construction searches [0.5]     */
+  int32_t refinements;    /* r refinement passes (Alg. 6) [2]; pass -1 for none        */
+  int32_t pq_cap;         /* prioq capacity of the construction searches [64]          */
+  int32_t visited_cap;    /* visited capacity of the construction searches [384]       */
+  int32_t max_iter;       /* iteration limit per layer [visited_cap]; <= visited_cap   */
+  int32_t no_sym_constraint; /* 1 disables the midpoint constraint of Sec. 4.2.1 [0]   */
+  void* stream;           /* hipStream_t for all work on this graph [default stream]   */
+} ggnn_build_params;
+
+typedef struct {
+  int64_t N;                    /* base points                                         */
+  int32_t D, K, L, s, g;        /* dims, out-degree, layers, segment size, growth      */
+  int32_t dtype, metric;
+  int64_t n[GGNN_MAX_LEVELS];   /* points per layer, n[0] = N, n[L-1] = s (Sec. 4.3)   */
+  float dnn_mean, dnn_max;      /* mean / max first-neighbour distance (Eq. 3, Eq. 4)  */
+  int64_t graph_bytes;          /* edges + translation tables + the two scalars        */
+  uint64_t seed;
+} ggnn_graph_desc;
+
+/* Per-phase time of a build in milliseconds, measured with HIP events on the graph's
+ * stream (cf. the paper's construction-time split, Sec. 5.2.2). */
+typedef struct {
+  float merge_ms, sym_ms, select_ms, stats_ms, total_ms;
+} ggnn_build_times;
+
+/* ---- construction (Alg. 3: BuildGraph; Alg. 6: RefineGraph) ------------------------ */
+
+/* Builds the whole hierarchy for float32 rows and L2 distance with default parameters.
+ * base_dev: N x D float32, device.  K: out-degree (2 <= K <= 64).  levels: L >= 2.
+ * seed: drives the bottom-layer partition and the top-layer selection.  *out receives a
+ * graph to be released with ggnn_free. */
+int ggnn_build(const float* base_dev, int64_t N, int32_t D, int32_t K, int32_t levels, uint64_t seed,
+               ggnn_graph** out);
+
+/* Same with explicit parameters (p may be NULL); base_dev has p->dtype elements. */
+int ggnn_build_ex(const void* base_dev, int64_t N, int32_t D, int32_t K, int32_t levels, uint64_t seed,
+                  const ggnn_build_params* p, ggnn_graph** out);
+
+/* Step-wise construction.  ggnn_graph_create allocates an empty graph (all edges -1, no
+ * tables); the steps below are exactly those ggnn_build_ex sequences:
+ *   for l_top = 0..L-1: if l_top > 0 select(l_top); for l_m = l_top..0: merge(l_top, l_m); sym(l_m)
+ *   then r times: for l_m = L-2..0: merge(L-1, l_m); sym(l_m)
+ * ggnn_select (Sec. 4.1): fills layer l_top (l_top >= 1) with s points per segment, taken
+ *   equally from the g child segments by weighted reservoir sampling with weight d_nn1.
+ * ggnn_merge (Alg. 3 Merge, Alg. 4): replaces the rows of layer l_m by the K nearest
+ *   neighbours found by searching from the top segment of layer l_top (exhaustively
+ *   inside the own segment when l_top == l_m); on layer 0 also updates d_nn1 and the
+ *   two statistics.
+ * ggnn_sym (Alg. 5, Sec. 4.2): inserts up to K - K/2 inverse links per row of `layer`. */
+int ggnn_graph_create(const void* base_dev, int64_t N, int32_t D, int32_t K, int32_t levels, uint64_t seed,
+                      const ggnn_build_params* p, ggnn_graph** out);
+int ggnn_select(ggnn_graph* g, int32_t l_top);
+int ggnn_merge(ggnn_graph* g, int32_t l_top, int32_t l_m);
+int ggnn_sym(ggnn_graph* g, int32_t layer);
+int ggnn_build_steps(ggnn_graph* g); /* the sequence above on a created graph */
+
+/* Times of the last ggnn_build* / ggnn_build_steps on this graph. */
+int ggnn_build_get_times(const ggnn_graph* g, ggnn_build_times* out);
+
+/* ---- query (Alg. 1, Alg. 2, Eq. 2; Sec. 4.4) --------------------------------------- */
+
+/* Answers Q queries.  queries_dev: Q x D elements of the graph's dtype, device.
+ * k results per query; beam: length of the best list the stopping rule looks at (the
+ * paper uses max(k, 10); the effective length is max(beam, k)); slack: tau_q of Eq. 2.
+ * ids_dev / dists_dev: Q x k, device; row q holds the results ascending by (distance,
+ * id), padded with id -1 / distance +inf.  Defaults: prioq 64, visited 384 (896 when
+ * beam >= 100), iteration limit = visited capacity, search drops from the top layer
+ * straight to the bottom layer (Sec. 4.4).  Runs on the graph's stream. */
+int ggnn_query(const ggnn_graph* g, const void* queries_dev, int64_t Q, int32_t k, int32_t beam, float slack,
+               int32_t* ids_dev, float* dists_dev);
+
+/* Same with every cache capacity explicit (0 = default as above).
+ * max_iter: iteration limit per layer, must be <= visited_cap so that visited never
+ * forgets a point.  every_layer: 0 = Sec. 4.4 shortcut, 1 = search every layer on the way
+ * down (Alg. 4).  stream: hipStream_t (NULL = the graph's stream).  counters_dev:
+ * optional Q x 2 uint32 (device): pops and distance evaluations per query.
+ * asynchronous != 0 returns right after the launch (no synchronisation). */
+int ggnn_query_ex(const ggnn_graph* g, const void* queries_dev, int64_t Q, int32_t k, int32_t beam, float slack,
+                  int32_t pq_cap, int32_t visited_cap, int32_t max_iter, int32_t every_layer, void* stream,
+                  int32_t* ids_dev, float* dists_dev, uint32_t* counters_dev, int32_t asynchronous);
+
+/* ---- graph access ------------------------------------------------------------------- */
+
+int ggnn_graph_info(const ggnn_graph* g, ggnn_graph_desc* out);
+
+/* Copies one layer to host arrays (any pointer may be NULL to skip it):
+ * edges_host n[layer] x K; to_lower_host / to_base_host n[layer] (layer >= 1 only: index of
+ * the point on the layer below, and its base row).  Layer-0 ids are base rows. */
+int ggnn_graph_export(const ggnn_graph* g, int32_t layer, int32_t* edges_host, int32_t* to_lower_host,
+                      int32_t* to_base_host);
+/* Overwrites one layer from host arrays (NULL = leave as is).  Rows must hold distinct
+ * ids in [0, n[layer]) followed only by -1 padding, and no self loop; tables must be in
+ * range.  Anything else is rejected with GGNN_ERR_INVALID. */
+int ggnn_graph_import(ggnn_graph* g, int32_t layer, const int32_t* edges_host, const int32_t* to_lower_host,
+                      const int32_t* to_base_host);
+/* d_nn1 per base row (N floats, host) and the two statistics derived from it. */
+int ggnn_graph_export_dnn(const ggnn_graph* g, float* dnn1_host, float* mean, float* max);
+int ggnn_graph_import_dnn(ggnn_graph* g, const float* dnn1_host, float mean, float max);
+/* number of inverse links each row of `layer` holds after the last ggnn_sym (host, n[layer]) */
+int ggnn_graph_export_inv_count(const ggnn_graph* g, int32_t layer, int32_t* count_host);
+
+void ggnn_free(ggnn_graph* g);
+const char* ggnn_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,238 @@
+"""ctypes binding of libggnn.so (include/ggnn.h): argument marshalling only.
+
+Every function takes torch tensors that live on the GPU (or numpy arrays for the host-side
+import / export calls) and passes their addresses on; all computation happens in the library.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+L2, COSINE = 0, 1
+F32, U8 = 0, 1
+MAX_LEVELS = 8
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libggnn.so")
+_lib = None
+
+
+class GgnnError(RuntimeError):
+    pass
+
+
+class BuildParams(C.Structure):
+    _fields_ = [("metric", C.c_int32), ("dtype", C.c_int32), ("segment_size", C.c_int32),
+                ("tau_build", C.c_float), ("refinements", C.c_int32), ("pq_cap", C.c_int32),
+                ("visited_cap", C.c_int32), ("max_iter", C.c_int32), ("no_sym_constraint", C.c_int32),
+                ("stream", C.c_void_p)]
+
+
+class GraphDesc(C.Structure):
+    _fields_ = [("N", C.c_int64), ("D", C.c_int32), ("K", C.c_int32), ("L", C.c_int32), ("s", C.c_int32),
+                ("g", C.c_int32), ("dtype", C.c_int32), ("metric", C.c_int32), ("n", C.c_int64 * MAX_LEVELS),
+                ("dnn_mean", C.c_float), ("dnn_max", C.c_float), ("graph_bytes", C.c_int64), ("seed", C.c_uint64)]
+
+
+class BuildTimes(C.Structure):
+    _fields_ = [("merge_ms", C.c_float), ("sym_ms", C.c_float), ("select_ms", C.c_float),
+                ("stats_ms", C.c_float), ("total_ms", C.c_float)]
+
+
+EXPORTS = [
+    "ggnn_build", "ggnn_build_ex", "ggnn_graph_create", "ggnn_select", "ggnn_merge", "ggnn_sym",
+    "ggnn_build_steps", "ggnn_build_get_times", "ggnn_query", "ggnn_query_ex", "ggnn_graph_info",
+    "ggnn_graph_export", "ggnn_graph_import", "ggnn_graph_export_dnn", "ggnn_graph_import_dnn",
+    "ggnn_graph_export_inv_count", "ggnn_free", "ggnn_last_error",
+]
+
+
+def lib():
+    """Loads libggnn.so.  There is no fallback: without the built library nothing runs."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise GgnnError("%s is missing: run `python -m paper_1912_01059_amd.build` (or __graft_entry__.build())"
+                            % _LIB_PATH)
+        L = C.CDLL(_LIB_PATH)
+        vp, i64, i32, u64, f32 = C.c_void_p, C.c_int64, C.c_int32, C.c_uint64, C.c_float
+        L.ggnn_build.argtypes = [vp, i64, i32, i32, i32, u64, C.POINTER(vp)]
+        L.ggnn_build_ex.argtypes = [vp, i64, i32, i32, i32, u64, C.POINTER(BuildParams), C.POINTER(vp)]
+        L.ggnn_graph_create.argtypes = [vp, i64, i32, i32, i32, u64, C.POINTER(BuildParams), C.POINTER(vp)]
+        L.ggnn_select.argtypes = [vp, i32]
+        L.ggnn_merge.argtypes = [vp, i32, i32]
+        L.ggnn_sym.argtypes = [vp, i32]
+        L.ggnn_build_steps.argtypes = [vp]
+        L.ggnn_build_get_times.argtypes = [vp, C.POINTER(BuildTimes)]
+        L.ggnn_query.argtypes = [vp, vp, i64, i32, i32, f32, vp, vp]
+        L.ggnn_query_ex.argtypes = [vp, vp, i64, i32, i32, f32, i32, i32, i32, i32, vp, vp, vp, vp, i32]
+        L.ggnn_graph_info.argtypes = [vp, C.POINTER(GraphDesc)]
+        L.ggnn_graph_export.argtypes = [vp, i32, vp, vp, vp]
+        L.ggnn_graph_import.argtypes = [vp, i32, vp, vp, vp]
+        L.ggnn_graph_export_dnn.argtypes = [vp, vp, C.POINTER(f32), C.POINTER(f32)]
+        L.ggnn_graph_import_dnn.argtypes = [vp, vp, f32, f32]
+        L.ggnn_graph_export_inv_count.argtypes = [vp, i32, vp]
+        L.ggnn_free.argtypes = [vp]
+        L.ggnn_free.restype = None
+        L.ggnn_last_error.restype = C.c_char_p
+        _lib = L
+    return _lib
+
+
+def last_error() -> str:
+    return lib().ggnn_last_error().decode()
+
+
+def _check(rc):
+    if rc != 0:
+        raise GgnnError("ggnn error %d: %s" % (rc, last_error()))
+
+
+def _dev_ptr(t):
+    import torch
+    assert isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous(), "need a contiguous GPU tensor"
+    return C.c_void_p(t.data_ptr())
+
+
+def _host_ptr(a):
+    if a is None:
+        return None
+    assert isinstance(a, np.ndarray) and a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def _dtype_code(t):
+    import torch
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.uint8:
+        return U8
+    raise TypeError("base must be float32 or uint8, got %s" % t.dtype)
+
+
+def _params(base, metric, segment_size, tau_build, refinements, pq_cap, visited_cap, max_iter, sym_constraint, stream):
+    p = BuildParams()
+    p.metric, p.dtype, p.segment_size = metric, _dtype_code(base), segment_size
+    p.tau_build = tau_build
+    p.refinements = -1 if refinements == 0 else refinements
+    p.pq_cap, p.visited_cap, p.max_iter = pq_cap, visited_cap, max_iter
+    p.no_sym_constraint = 0 if sym_constraint else 1
+    p.stream = stream
+    return p
+
+
+class Graph:
+    """Handle of a ggnn_graph.  Keeps the base tensor alive (the library borrows it)."""
+
+    def __init__(self, handle, base):
+        self.h = handle
+        self.base = base
+        d = GraphDesc()
+        _check(lib().ggnn_graph_info(self.h, C.byref(d)))
+        self.N, self.D, self.K, self.L, self.s, self.g = d.N, d.D, d.K, d.L, d.s, d.g
+        self.n = [d.n[l] for l in range(d.L)]
+        self.graph_bytes = d.graph_bytes
+
+    def __del__(self):
+        try:
+            if getattr(self, "h", None) and _lib is not None:
+                _lib.ggnn_free(self.h)
+                self.h = None
+        except Exception:  # interpreter shutdown
+            pass
+
+    def info(self):
+        d = GraphDesc()
+        _check(lib().ggnn_graph_info(self.h, C.byref(d)))
+        return d
+
+    # construction steps
+    def select(self, l_top):
+        _check(lib().ggnn_select(self.h, l_top))
+
+    def merge(self, l_top, l_m):
+        _check(lib().ggnn_merge(self.h, l_top, l_m))
+
+    def sym(self, layer):
+        _check(lib().ggnn_sym(self.h, layer))
+
+    def build_steps(self):
+        _check(lib().ggnn_build_steps(self.h))
+        return self
+
+    def times(self):
+        t = BuildTimes()
+        _check(lib().ggnn_build_get_times(self.h, C.byref(t)))
+        return {k: getattr(t, k) for k, _ in BuildTimes._fields_}
+
+    # host-side access
+    def export_layer(self, layer):
+        e = np.empty((self.n[layer], self.K), np.int32)
+        tl = np.empty(self.n[layer], np.int32) if layer >= 1 else None
+        tb = np.empty(self.n[layer], np.int32) if layer >= 1 else None
+        _check(lib().ggnn_graph_export(self.h, layer, _host_ptr(e), _host_ptr(tl), _host_ptr(tb)))
+        return e, tl, tb
+
+    def import_layer(self, layer, edges=None, to_lower=None, to_base=None):
+        conv = lambda a: None if a is None else np.ascontiguousarray(a, np.int32)
+        edges, to_lower, to_base = conv(edges), conv(to_lower), conv(to_base)
+        _check(lib().ggnn_graph_import(self.h, layer, _host_ptr(edges), _host_ptr(to_lower), _host_ptr(to_base)))
+
+    def export_dnn(self):
+        d = np.empty(self.N, np.float32)
+        mean, mx = C.c_float(), C.c_float()
+        _check(lib().ggnn_graph_export_dnn(self.h, _host_ptr(d), C.byref(mean), C.byref(mx)))
+        return d, mean.value, mx.value
+
+    def import_dnn(self, dnn1, mean, mx):
+        dnn1 = None if dnn1 is None else np.ascontiguousarray(dnn1, np.float32)
+        _check(lib().ggnn_graph_import_dnn(self.h, _host_ptr(dnn1), float(mean), float(mx)))
+
+    def export_inv_count(self, layer):
+        c = np.empty(self.n[layer], np.int32)
+        _check(lib().ggnn_graph_export_inv_count(self.h, layer, _host_ptr(c)))
+        return c
+
+    def query(self, queries, k, beam, slack, pq_cap=0, visited_cap=0, max_iter=0, every_layer=False,
+              counters=False, out=None, stream=None, asynchronous=False):
+        return query(self, queries, k, beam, slack, pq_cap, visited_cap, max_iter, every_layer, counters, out,
+                     stream, asynchronous)
+
+
+def graph_create(base, K, levels, seed=42, metric=L2, segment_size=0, tau_build=0.0, refinements=2, pq_cap=0,
+                 visited_cap=0, max_iter=0, sym_constraint=True, stream=None) -> Graph:
+    """ggnn_graph_create: an empty graph over `base` (N x D GPU tensor, float32 or uint8)."""
+    p = _params(base, metric, segment_size, tau_build, refinements, pq_cap, visited_cap, max_iter, sym_constraint, stream)
+    h = C.c_void_p()
+    _check(lib().ggnn_graph_create(_dev_ptr(base), base.shape[0], base.shape[1], K, levels, seed, C.byref(p), C.byref(h)))
+    return Graph(h, base)
+
+
+def build(base, K, levels, seed=42, metric=L2, segment_size=0, tau_build=0.0, refinements=2, pq_cap=0,
+          visited_cap=0, max_iter=0, sym_constraint=True, stream=None) -> Graph:
+    """ggnn_build_ex: the whole construction (Alg. 3 followed by r passes of Alg. 6)."""
+    p = _params(base, metric, segment_size, tau_build, refinements, pq_cap, visited_cap, max_iter, sym_constraint, stream)
+    h = C.c_void_p()
+    _check(lib().ggnn_build_ex(_dev_ptr(base), base.shape[0], base.shape[1], K, levels, seed, C.byref(p), C.byref(h)))
+    return Graph(h, base)
+
+
+def query(graph, queries, k, beam, slack, pq_cap=0, visited_cap=0, max_iter=0, every_layer=False,
+          counters=False, out=None, stream=None, asynchronous=False):
+    """ggnn_query_ex.  Returns (ids, dists[, counters]) as GPU tensors; `out` = (ids, dists) reuses buffers."""
+    import torch
+    Q = queries.shape[0]
+    if out is None:
+        ids = torch.empty((Q, k), dtype=torch.int32, device=queries.device)
+        dists = torch.empty((Q, k), dtype=torch.float32, device=queries.device)
+    else:
+        ids, dists = out
+    cnt = torch.zeros((Q, 2), dtype=torch.int32, device=queries.device) if counters else None
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream
+    _check(lib().ggnn_query_ex(graph.h, _dev_ptr(queries), Q, k, beam, slack, pq_cap, visited_cap, max_iter,
+                               1 if every_layer else 0, C.c_void_p(stream), _dev_ptr(ids), _dev_ptr(dists),
+                               _dev_ptr(cnt) if counters else None, 1 if asynchronous else 0))
+    return (ids, dists, cnt) if counters else (ids, dists)

@@ -1,0 +1,545 @@
+// C ABI of the library (see include/ggnn.h): argument checks, device memory of the graph,
+// and the sequencing of kernels for construction (Alg. 3, Alg. 6) and query (Alg. 1).
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "ggnn.h"
+#include "ggnn_launch.h"
+
+using namespace ggnn;
+
+static_assert(GGNN_ROW_LANES == kRowLanes, "public constant and kernels disagree");
+static_assert(GGNN_MAX_LEVELS == kMaxLevels, "public constant and kernels disagree");
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                              \
+  do {                                                                                             \
+    hipError_t e_ = (expr);                                                                        \
+    if (e_ != hipSuccess) return fail(GGNN_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_));       \
+  } while (0)
+
+constexpr size_t kMaxLds = 64 * 1024;
+
+uint64_t mix64_host(uint64_t x) {
+  x ^= x >> 30; x *= 0xBF58476D1CE4E5B9ull;
+  x ^= x >> 27; x *= 0x94D049BB133111EBull;
+  x ^= x >> 31;
+  return x;
+}
+
+int64_t ipow(int64_t b, int e) {
+  int64_t r = 1;
+  for (int i = 0; i < e; i++) r *= b;
+  return r;
+}
+
+// Sec. 4.3 / appendix "Graph Size": growth factor and layer sizes
+int geometry(int64_t N, int s, int L, int* g_out, int64_t* n, int64_t* G) {
+  const double root = pow((double)N / (double)s, 1.0 / (double)(L - 1));
+  int64_t cand[2] = {(int64_t)floor(root), (int64_t)ceil(root)};
+  int64_t g = -1;
+  double err = 0.0;
+  for (int i = 0; i < 2; i++) {
+    int64_t c = cand[i] < 1 ? 1 : cand[i];
+    double e = fabs((double)N / (double)ipow(c, L - 1) - (double)s);
+    if (g < 0 || e < err) { g = c; err = e; }
+  }
+  for (int l = 0; l < L; l++) {
+    G[l] = ipow(g, L - 1 - l);
+    n[l] = (l == 0) ? N : (int64_t)s * G[l];
+  }
+  if (G[0] > N) return -1;
+  const int64_t s0_min = N / G[0];
+  const int64_t share_max = ((int64_t)s + g - 1) / g;
+  if (s0_min < share_max || s0_min < 2) return -1;
+  if (L > 2 && n[1] > N) return -1;
+  *g_out = (int)g;
+  return 0;
+}
+
+int next_pow2(int v) {
+  int p = 1;
+  while (p < v) p <<= 1;
+  return p;
+}
+
+}  // namespace
+
+struct ggnn_graph {
+  int64_t N = 0;
+  int D = 0, K = 0, L = 0, s = 0, g = 0;
+  int dtype = 0, metric = 0;
+  uint64_t seed = 0;
+  int64_t n[kMaxLevels] = {0}, G[kMaxLevels] = {0};
+  int32_t* edges[kMaxLevels] = {nullptr};
+  int32_t* to_lower[kMaxLevels] = {nullptr};
+  int32_t* to_base[kMaxLevels] = {nullptr};
+  int32_t* inv_count[kMaxLevels] = {nullptr};
+  int32_t* edge_tmp = nullptr;  // N*K, the buffer a merge writes before the swap
+  float* dnn1 = nullptr;        // N
+  float* stats_dev = nullptr;   // 2
+  double* stats_partial = nullptr;
+  float stats[2] = {0.0f, 0.0f};
+  const void* base = nullptr;   // borrowed
+  float* norm = nullptr;        // cosine: owned unit-length copy
+  hipStream_t stream = nullptr;
+  // construction parameters
+  float tau_build = 0.5f;
+  int refinements = 2, pq_cap = 64, visited_cap = 384, max_iter = 384;
+  float w_mid = 0.4f;
+  SymBuffers sb = {};
+  bool sb_ready = false;
+  ggnn_build_times times = {};
+};
+
+namespace {
+
+GraphDev device_view(const ggnn_graph* g) {
+  GraphDev G = {};
+  G.rows = (const uint8_t*)(g->norm ? (const void*)g->norm : g->base);
+  G.N = g->N; G.D = g->D; G.K = g->K; G.L = g->L; G.s = g->s; G.g = g->g;
+  const int esize = (g->norm || g->dtype == GGNN_F32) ? 4 : 1;
+  G.row_bytes = g->D * esize;
+  G.nchunks = G.row_bytes / 16;
+  for (int l = 0; l < g->L; l++) {
+    G.n[l] = g->n[l];
+    G.edges[l] = g->edges[l];
+    G.to_lower[l] = g->to_lower[l];
+    G.to_base[l] = g->to_base[l];
+  }
+  G.G0 = g->G[0];
+  int h = 1;
+  while ((((int64_t)1) << (2 * h)) < g->N) h++;
+  G.fbits = h;
+  for (int r = 0; r < 4; r++) G.fkey[r] = (uint32_t)mix64_host(g->seed + 0x9E3779B97F4A7C15ull * (uint64_t)(r + 1));
+  G.seed = g->seed;
+  return G;
+}
+int row_dtype(const ggnn_graph* g) { return g->norm ? GGNN_F32 : g->dtype; }
+
+int make_search_params(int B, int P, int V, int max_iter, float tau, float dnn, SearchParams* sp) {
+  if (B < 1 || P < 1 || V < 1 || max_iter < 0) return fail(GGNN_ERR_INVALID, "cache capacities must be positive");
+  if (max_iter > V) return fail(GGNN_ERR_INVALID, "max_iter (%d) must not exceed visited_cap (%d)", max_iter, V);
+  sp->B = B; sp->P = P; sp->max_iter = max_iter;
+  sp->H = next_pow2(2 * (max_iter > 0 ? max_iter : 1));
+  if (sp->H < 64) sp->H = 64;
+  sp->tau = tau; sp->dnn = dnn;
+  if (cache_lds_bytes(sp->B, sp->P, sp->H) > kMaxLds)
+    return fail(GGNN_ERR_LIMIT, "cache of best=%d prioq=%d visited=%d needs %zu bytes of LDS, limit %zu", B, P, V,
+                cache_lds_bytes(sp->B, sp->P, sp->H), kMaxLds);
+  return GGNN_OK;
+}
+
+int ensure_sym_buffers(ggnn_graph* g) {
+  if (g->sb_ready) return GGNN_OK;
+  const int64_t n = g->n[0];
+  const int ksym = g->K - g->K / 2;
+  SymBuffers& sb = g->sb;
+  HIP_TRY(hipMalloc(&sb.inv, sizeof(int32_t) * n * ksym));
+  HIP_TRY(hipMalloc(&sb.ninv, sizeof(int32_t) * n));
+  HIP_TRY(hipMalloc(&sb.pref, sizeof(u64) * n * g->K));
+  HIP_TRY(hipMalloc(&sb.npref, sizeof(int32_t) * n));
+  HIP_TRY(hipMalloc(&sb.ptr, sizeof(int32_t) * n));
+  HIP_TRY(hipMalloc(&sb.state, sizeof(int32_t) * n));
+  HIP_TRY(hipMalloc(&sb.hold, sizeof(int32_t) * n * ksym));
+  HIP_TRY(hipMalloc(&sb.nhold, sizeof(int32_t) * n));
+  HIP_TRY(hipMalloc(&sb.head, sizeof(int32_t) * n));
+  HIP_TRY(hipMalloc(&sb.next, sizeof(int32_t) * n));
+  HIP_TRY(hipMalloc(&sb.pending, sizeof(int32_t)));
+  g->sb_ready = true;
+  return GGNN_OK;
+}
+
+void release_sym_buffers(ggnn_graph* g) {
+  SymBuffers& sb = g->sb;
+  hipFree(sb.inv); hipFree(sb.ninv); hipFree(sb.pref); hipFree(sb.npref); hipFree(sb.ptr); hipFree(sb.state);
+  hipFree(sb.hold); hipFree(sb.nhold); hipFree(sb.head); hipFree(sb.next); hipFree(sb.pending);
+  sb = SymBuffers{};
+  g->sb_ready = false;
+}
+
+struct PhaseTimer {
+  hipEvent_t a = nullptr, b = nullptr;
+  hipStream_t st;
+  explicit PhaseTimer(hipStream_t s) : st(s) {
+    hipEventCreate(&a);
+    hipEventCreate(&b);
+    hipEventRecord(a, st);
+  }
+  float stop() {
+    float ms = 0.0f;
+    hipEventRecord(b, st);
+    hipEventSynchronize(b);
+    hipEventElapsedTime(&ms, a, b);
+    return ms;
+  }
+  ~PhaseTimer() {
+    hipEventDestroy(a);
+    hipEventDestroy(b);
+  }
+};
+
+}  // namespace
+
+extern "C" {
+
+const char* ggnn_last_error(void) { return g_err; }
+
+void ggnn_free(ggnn_graph* g) {
+  if (!g) return;
+  for (int l = 0; l < kMaxLevels; l++) {
+    hipFree(g->edges[l]); hipFree(g->to_lower[l]); hipFree(g->to_base[l]); hipFree(g->inv_count[l]);
+  }
+  hipFree(g->edge_tmp); hipFree(g->dnn1); hipFree(g->stats_dev); hipFree(g->stats_partial); hipFree(g->norm);
+  release_sym_buffers(g);
+  delete g;
+}
+
+int ggnn_graph_create(const void* base_dev, int64_t N, int32_t D, int32_t K, int32_t levels, uint64_t seed,
+                      const ggnn_build_params* p, ggnn_graph** out) {
+  if (!out) return fail(GGNN_ERR_INVALID, "out is NULL");
+  *out = nullptr;
+  if (!base_dev) return fail(GGNN_ERR_INVALID, "base_dev is NULL");
+  ggnn_build_params dflt;
+  memset(&dflt, 0, sizeof(dflt));
+  if (!p) p = &dflt;
+  const int dtype = p->dtype, metric = p->metric;
+  if (dtype != GGNN_F32 && dtype != GGNN_U8) return fail(GGNN_ERR_INVALID, "unknown dtype %d", dtype);
+  if (metric != GGNN_L2 && metric != GGNN_COSINE) return fail(GGNN_ERR_INVALID, "unknown metric %d", metric);
+  if (metric == GGNN_COSINE && dtype != GGNN_F32) return fail(GGNN_ERR_INVALID, "cosine distance needs float32 rows");
+  const int s = p->segment_size ? p->segment_size : 32;
+  if (s < 2 || s > kWave) return fail(GGNN_ERR_INVALID, "segment_size %d outside [2, 64]", s);
+  if (K < 2 || K > kWave) return fail(GGNN_ERR_INVALID, "K = %d outside [2, 64]", K);
+  if (levels < 2 || levels > kMaxLevels) return fail(GGNN_ERR_INVALID, "levels = %d outside [2, %d]", levels, kMaxLevels);
+  if (N < 2 || N > 0x7FFFFFFFll) return fail(GGNN_ERR_INVALID, "N = %lld outside [2, 2^31)", (long long)N);
+  const int esize = dtype == GGNN_F32 ? 4 : 1;
+  if (D < 1 || (D * esize) % 16 != 0) return fail(GGNN_ERR_INVALID, "a row of D = %d elements is not a multiple of 16 bytes", D);
+  const int need = (D * esize / 16 + kRowLanes - 1) / kRowLanes;
+  if ((dtype == GGNN_F32 && need > 8) || (dtype == GGNN_U8 && need > 2))
+    return fail(GGNN_ERR_INVALID, "D = %d too large (float32: <= 256, uint8: <= 256)", D);
+  if (((uintptr_t)base_dev) % 16 != 0) return fail(GGNN_ERR_INVALID, "base_dev is not 16-byte aligned");
+
+  ggnn_graph* g = new (std::nothrow) ggnn_graph();
+  if (!g) return fail(GGNN_ERR_MEMORY, "host allocation failed");
+  g->N = N; g->D = D; g->K = K; g->L = levels; g->s = s; g->dtype = dtype; g->metric = metric; g->seed = seed;
+  g->base = base_dev;
+  g->stream = (hipStream_t)p->stream;
+  g->tau_build = p->tau_build > 0.0f ? p->tau_build : 0.5f;
+  g->refinements = p->refinements < 0 ? 0 : (p->refinements == 0 ? 2 : p->refinements);
+  g->pq_cap = p->pq_cap > 0 ? p->pq_cap : 64;
+  g->visited_cap = p->visited_cap > 0 ? p->visited_cap : 384;
+  g->max_iter = p->max_iter > 0 ? p->max_iter : g->visited_cap;
+  g->w_mid = p->no_sym_constraint ? 0.0f : 0.4f;
+  if (geometry(N, s, levels, &g->g, g->n, g->G) != 0) {
+    delete g;
+    return fail(GGNN_ERR_INVALID, "N = %lld, s = %d, levels = %d admit no hierarchy", (long long)N, s, levels);
+  }
+  if ((N + g->G[0] - 1) / g->G[0] > kWave) {
+    delete g;
+    return fail(GGNN_ERR_INVALID, "bottom segments would hold more than 64 points");
+  }
+  SearchParams sp;
+  int rc = make_search_params(K, g->pq_cap, g->visited_cap, g->max_iter, g->tau_build, 0.0f, &sp);
+  if (rc != GGNN_OK) { delete g; return rc; }
+
+#define CREATE_TRY(expr)                                                                   \
+  do {                                                                                     \
+    hipError_t e_ = (expr);                                                                \
+    if (e_ != hipSuccess) {                                                                \
+      ggnn_free(g);                                                                        \
+      return fail(e_ == hipErrorOutOfMemory ? GGNN_ERR_MEMORY : GGNN_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    }                                                                                      \
+  } while (0)
+  for (int l = 0; l < levels; l++) {
+    const int64_t cnt = g->n[l] * K;
+    CREATE_TRY(hipMalloc(&g->edges[l], sizeof(int32_t) * cnt));
+    CREATE_TRY(launch_fill_i32(g->edges[l], cnt, -1, g->stream));
+    CREATE_TRY(hipMalloc(&g->inv_count[l], sizeof(int32_t) * g->n[l]));
+    CREATE_TRY(launch_fill_i32(g->inv_count[l], g->n[l], 0, g->stream));
+    if (l >= 1) {
+      CREATE_TRY(hipMalloc(&g->to_lower[l], sizeof(int32_t) * g->n[l]));
+      CREATE_TRY(hipMalloc(&g->to_base[l], sizeof(int32_t) * g->n[l]));
+      CREATE_TRY(launch_fill_i32(g->to_lower[l], g->n[l], 0, g->stream));
+      CREATE_TRY(launch_fill_i32(g->to_base[l], g->n[l], 0, g->stream));
+    }
+  }
+  CREATE_TRY(hipMalloc(&g->edge_tmp, sizeof(int32_t) * N * K));
+  CREATE_TRY(hipMalloc(&g->dnn1, sizeof(float) * N));
+  CREATE_TRY(launch_fill_i32((int32_t*)g->dnn1, N, 0, g->stream));
+  CREATE_TRY(hipMalloc(&g->stats_dev, sizeof(float) * 2));
+  CREATE_TRY(hipMalloc(&g->stats_partial, sizeof(double) * 2 * 1024));
+  if (metric == GGNN_COSINE) {
+    CREATE_TRY(hipMalloc(&g->norm, sizeof(float) * N * D));
+    CREATE_TRY(launch_normalise(base_dev, dtype, N, D, g->norm, g->stream));
+  }
+  CREATE_TRY(hipStreamSynchronize(g->stream));
+#undef CREATE_TRY
+  *out = g;
+  return GGNN_OK;
+}
+
+int ggnn_select(ggnn_graph* g, int32_t l_top) {
+  if (!g) return fail(GGNN_ERR_INVALID, "graph is NULL");
+  if (l_top < 1 || l_top >= g->L) return fail(GGNN_ERR_INVALID, "l_top = %d outside [1, %d)", l_top, g->L);
+  PhaseTimer t(g->stream);
+  GraphDev G = device_view(g);
+  HIP_TRY(launch_select(G, l_top, g->dnn1, g->to_lower[l_top], g->to_base[l_top], g->stream));
+  HIP_TRY(hipStreamSynchronize(g->stream));
+  g->times.select_ms += t.stop();
+  return GGNN_OK;
+}
+
+int ggnn_merge(ggnn_graph* g, int32_t l_top, int32_t l_m) {
+  if (!g) return fail(GGNN_ERR_INVALID, "graph is NULL");
+  if (l_top < 0 || l_top >= g->L || l_m < 0 || l_m > l_top)
+    return fail(GGNN_ERR_INVALID, "merge(%d, %d) outside the hierarchy", l_top, l_m);
+  SearchParams sp;
+  // during construction the mean first-neighbour distance stands in for the maximum (Eq. 4)
+  int rc = make_search_params(g->K, g->pq_cap, g->visited_cap, g->max_iter, g->tau_build, g->stats[0], &sp);
+  if (rc != GGNN_OK) return rc;
+  {
+    PhaseTimer t(g->stream);
+    GraphDev G = device_view(g);
+    HIP_TRY(launch_merge(G, row_dtype(g), g->metric, l_top, l_m, sp, g->edge_tmp, g->dnn1, g->stream));
+    // the buffer becomes the layer (inverse links of the layer are thereby discarded)
+    HIP_TRY(hipMemcpyAsync(g->edges[l_m], g->edge_tmp, sizeof(int32_t) * g->n[l_m] * g->K, hipMemcpyDeviceToDevice, g->stream));
+    HIP_TRY(launch_fill_i32(g->inv_count[l_m], g->n[l_m], 0, g->stream));
+    HIP_TRY(hipStreamSynchronize(g->stream));
+    g->times.merge_ms += t.stop();
+  }
+  if (l_m == 0) {
+    PhaseTimer t(g->stream);
+    HIP_TRY(launch_stats(g->dnn1, g->N, g->stats_partial, g->stats_dev, g->stream));
+    HIP_TRY(hipMemcpyAsync(g->stats, g->stats_dev, sizeof(float) * 2, hipMemcpyDeviceToHost, g->stream));
+    HIP_TRY(hipStreamSynchronize(g->stream));
+    g->times.stats_ms += t.stop();
+  }
+  return GGNN_OK;
+}
+
+int ggnn_sym(ggnn_graph* g, int32_t layer) {
+  if (!g) return fail(GGNN_ERR_INVALID, "graph is NULL");
+  if (layer < 0 || layer >= g->L) return fail(GGNN_ERR_INVALID, "layer %d outside [0, %d)", layer, g->L);
+  int rc = ensure_sym_buffers(g);
+  if (rc != GGNN_OK) return rc;
+  SearchParams sp;
+  rc = make_search_params(g->K, g->pq_cap, g->visited_cap, g->max_iter, g->tau_build, g->stats[0], &sp);
+  if (rc != GGNN_OK) return rc;
+  PhaseTimer t(g->stream);
+  GraphDev G = device_view(g);
+  const SymBuffers& sb = g->sb;
+  const int64_t n = g->n[layer];
+  const int knn = g->K / 2;
+  HIP_TRY(launch_fill_i32(sb.ninv, n, 0, g->stream));
+  HIP_TRY(launch_fill_i32(sb.nhold, n, 0, g->stream));
+  HIP_TRY(launch_fill_i32(sb.head, n, -1, g->stream));
+  for (int round = 0; round < knn; round++) {
+    HIP_TRY(launch_sym_search(G, row_dtype(g), g->metric, layer, round, g->w_mid, sp, sb, g->stream));
+    bool first = true;
+    for (;;) {
+      HIP_TRY(launch_fill_i32(sb.pending, 1, 0, g->stream));
+      if (first) HIP_TRY(launch_sym_propose_first(G, layer, sb, sp.B, g->stream));
+      else HIP_TRY(launch_sym_propose(G, layer, sb, sp.B, g->stream));
+      first = false;
+      HIP_TRY(launch_sym_resolve(G, layer, sb, sp.B, g->stream));
+      int32_t pending = 0;
+      HIP_TRY(hipMemcpyAsync(&pending, sb.pending, sizeof(int32_t), hipMemcpyDeviceToHost, g->stream));
+      HIP_TRY(hipStreamSynchronize(g->stream));
+      if (pending == 0) break;
+    }
+    HIP_TRY(launch_sym_commit(G, layer, sb, g->stream));
+  }
+  HIP_TRY(launch_sym_apply(G, layer, sb, g->edges[layer], g->inv_count[layer], g->stream));
+  HIP_TRY(hipStreamSynchronize(g->stream));
+  g->times.sym_ms += t.stop();
+  return GGNN_OK;
+}
+
+int ggnn_build_steps(ggnn_graph* g) {
+  if (!g) return fail(GGNN_ERR_INVALID, "graph is NULL");
+  g->times = ggnn_build_times{};
+  PhaseTimer total(g->stream);
+  int rc;
+  for (int l_top = 0; l_top < g->L; l_top++) {
+    if (l_top > 0 && (rc = ggnn_select(g, l_top)) != GGNN_OK) return rc;
+    for (int l_m = l_top; l_m >= 0; l_m--) {
+      if ((rc = ggnn_merge(g, l_top, l_m)) != GGNN_OK) return rc;
+      if ((rc = ggnn_sym(g, l_m)) != GGNN_OK) return rc;
+    }
+  }
+  for (int r = 0; r < g->refinements; r++) {
+    for (int l_m = g->L - 2; l_m >= 0; l_m--) {
+      if ((rc = ggnn_merge(g, g->L - 1, l_m)) != GGNN_OK) return rc;
+      if ((rc = ggnn_sym(g, l_m)) != GGNN_OK) return rc;
+    }
+  }
+  g->times.total_ms = total.stop();
+  return GGNN_OK;
+}
+
+int ggnn_build_ex(const void* base_dev, int64_t N, int32_t D, int32_t K, int32_t levels, uint64_t seed,
+                  const ggnn_build_params* p, ggnn_graph** out) {
+  int rc = ggnn_graph_create(base_dev, N, D, K, levels, seed, p, out);
+  if (rc != GGNN_OK) return rc;
+  rc = ggnn_build_steps(*out);
+  if (rc != GGNN_OK) {
+    ggnn_free(*out);
+    *out = nullptr;
+    return rc;
+  }
+  // the construction buffers are not needed for queries
+  release_sym_buffers(*out);
+  return GGNN_OK;
+}
+
+int ggnn_build(const float* base_dev, int64_t N, int32_t D, int32_t K, int32_t levels, uint64_t seed,
+               ggnn_graph** out) {
+  return ggnn_build_ex(base_dev, N, D, K, levels, seed, nullptr, out);
+}
+
+int ggnn_build_get_times(const ggnn_graph* g, ggnn_build_times* out) {
+  if (!g || !out) return fail(GGNN_ERR_INVALID, "NULL argument");
+  *out = g->times;
+  return GGNN_OK;
+}
+
+int ggnn_query_ex(const ggnn_graph* g, const void* queries_dev, int64_t Q, int32_t k, int32_t beam, float slack,
+                  int32_t pq_cap, int32_t visited_cap, int32_t max_iter, int32_t every_layer, void* stream,
+                  int32_t* ids_dev, float* dists_dev, uint32_t* counters_dev, int32_t asynchronous) {
+  if (!g) return fail(GGNN_ERR_INVALID, "graph is NULL");
+  if (Q < 0 || Q > 0x7FFFFFFFll) return fail(GGNN_ERR_INVALID, "Q = %lld outside [0, 2^31)", (long long)Q);
+  if (Q == 0) return GGNN_OK;
+  if (!queries_dev || !ids_dev || !dists_dev) return fail(GGNN_ERR_INVALID, "NULL device pointer");
+  if (((uintptr_t)queries_dev) % 16 != 0) return fail(GGNN_ERR_INVALID, "queries_dev is not 16-byte aligned");
+  if (k < 1) return fail(GGNN_ERR_INVALID, "k = %d must be positive", k);
+  if (beam < 0 || !(slack >= 0.0f)) return fail(GGNN_ERR_INVALID, "beam and slack must not be negative");
+  const int B = beam > k ? beam : k;
+  const int P = pq_cap > 0 ? pq_cap : 64;
+  const int V = visited_cap > 0 ? visited_cap : (B >= 100 ? 896 : 384);
+  const int it = max_iter > 0 ? max_iter : V;
+  SearchParams sp;
+  // user queries bound the slack by the maximum first-neighbour distance (Eq. 2, Eq. 3)
+  int rc = make_search_params(B, P, V, it, slack, g->stats[1], &sp);
+  if (rc != GGNN_OK) return rc;
+  hipStream_t st = stream ? (hipStream_t)stream : g->stream;
+  GraphDev G = device_view(g);
+  if (g->metric == GGNN_COSINE && g->dtype != GGNN_F32) return fail(GGNN_ERR_INVALID, "cosine needs float32 queries");
+  HIP_TRY(launch_query(G, row_dtype(g), g->metric, queries_dev, Q, k, sp, every_layer ? 1 : 0, ids_dev, dists_dev,
+                       counters_dev, st));
+  if (!asynchronous) HIP_TRY(hipStreamSynchronize(st));
+  return GGNN_OK;
+}
+
+int ggnn_query(const ggnn_graph* g, const void* queries_dev, int64_t Q, int32_t k, int32_t beam, float slack,
+               int32_t* ids_dev, float* dists_dev) {
+  return ggnn_query_ex(g, queries_dev, Q, k, beam, slack, 0, 0, 0, 0, nullptr, ids_dev, dists_dev, nullptr, 0);
+}
+
+int ggnn_graph_info(const ggnn_graph* g, ggnn_graph_desc* out) {
+  if (!g || !out) return fail(GGNN_ERR_INVALID, "NULL argument");
+  memset(out, 0, sizeof(*out));
+  out->N = g->N; out->D = g->D; out->K = g->K; out->L = g->L; out->s = g->s; out->g = g->g;
+  out->dtype = g->dtype; out->metric = g->metric; out->seed = g->seed;
+  int64_t upper = 0;
+  for (int l = 0; l < g->L; l++) {
+    out->n[l] = g->n[l];
+    if (l >= 1) upper += g->n[l];
+  }
+  out->dnn_mean = g->stats[0];
+  out->dnn_max = g->stats[1];
+  // appendix "Graph Size": edge lists, two translation tables per upper point, two scalars
+  out->graph_bytes = ((g->N + upper) * g->K + 2 * upper + 2) * 4;
+  return GGNN_OK;
+}
+
+int ggnn_graph_export(const ggnn_graph* g, int32_t layer, int32_t* edges_host, int32_t* to_lower_host,
+                      int32_t* to_base_host) {
+  if (!g) return fail(GGNN_ERR_INVALID, "graph is NULL");
+  if (layer < 0 || layer >= g->L) return fail(GGNN_ERR_INVALID, "layer %d outside [0, %d)", layer, g->L);
+  if ((to_lower_host || to_base_host) && layer == 0) return fail(GGNN_ERR_INVALID, "layer 0 has no translation tables");
+  HIP_TRY(hipStreamSynchronize(g->stream));
+  if (edges_host) HIP_TRY(hipMemcpy(edges_host, g->edges[layer], sizeof(int32_t) * g->n[layer] * g->K, hipMemcpyDeviceToHost));
+  if (to_lower_host) HIP_TRY(hipMemcpy(to_lower_host, g->to_lower[layer], sizeof(int32_t) * g->n[layer], hipMemcpyDeviceToHost));
+  if (to_base_host) HIP_TRY(hipMemcpy(to_base_host, g->to_base[layer], sizeof(int32_t) * g->n[layer], hipMemcpyDeviceToHost));
+  return GGNN_OK;
+}
+
+int ggnn_graph_import(ggnn_graph* g, int32_t layer, const int32_t* edges_host, const int32_t* to_lower_host,
+                      const int32_t* to_base_host) {
+  if (!g) return fail(GGNN_ERR_INVALID, "graph is NULL");
+  if (layer < 0 || layer >= g->L) return fail(GGNN_ERR_INVALID, "layer %d outside [0, %d)", layer, g->L);
+  if ((to_lower_host || to_base_host) && layer == 0) return fail(GGNN_ERR_INVALID, "layer 0 has no translation tables");
+  const int64_t n = g->n[layer];
+  const int K = g->K;
+  if (edges_host) {
+    // the kernels rely on these properties: check them here, on the host
+    for (int64_t i = 0; i < n; i++) {
+      const int32_t* row = edges_host + i * K;
+      bool ended = false;
+      for (int a = 0; a < K; a++) {
+        if (row[a] == -1) { ended = true; continue; }
+        if (ended || row[a] < 0 || row[a] >= n || row[a] == i)
+          return fail(GGNN_ERR_INVALID, "layer %d row %lld entry %d is invalid", layer, (long long)i, a);
+        for (int b = 0; b < a; b++)
+          if (row[b] == row[a]) return fail(GGNN_ERR_INVALID, "layer %d row %lld repeats id %d", layer, (long long)i, row[a]);
+      }
+    }
+  }
+  const int64_t n_below = layer >= 1 ? g->n[layer - 1] : 0;
+  if (to_lower_host)
+    for (int64_t i = 0; i < n; i++)
+      if (to_lower_host[i] < 0 || to_lower_host[i] >= n_below) return fail(GGNN_ERR_INVALID, "to_lower[%lld] out of range", (long long)i);
+  if (to_base_host)
+    for (int64_t i = 0; i < n; i++)
+      if (to_base_host[i] < 0 || to_base_host[i] >= g->N) return fail(GGNN_ERR_INVALID, "to_base[%lld] out of range", (long long)i);
+  HIP_TRY(hipStreamSynchronize(g->stream));
+  if (edges_host) HIP_TRY(hipMemcpy(g->edges[layer], edges_host, sizeof(int32_t) * n * K, hipMemcpyHostToDevice));
+  if (to_lower_host) HIP_TRY(hipMemcpy(g->to_lower[layer], to_lower_host, sizeof(int32_t) * n, hipMemcpyHostToDevice));
+  if (to_base_host) HIP_TRY(hipMemcpy(g->to_base[layer], to_base_host, sizeof(int32_t) * n, hipMemcpyHostToDevice));
+  return GGNN_OK;
+}
+
+int ggnn_graph_export_dnn(const ggnn_graph* g, float* dnn1_host, float* mean, float* max) {
+  if (!g) return fail(GGNN_ERR_INVALID, "graph is NULL");
+  HIP_TRY(hipStreamSynchronize(g->stream));
+  if (dnn1_host) HIP_TRY(hipMemcpy(dnn1_host, g->dnn1, sizeof(float) * g->N, hipMemcpyDeviceToHost));
+  if (mean) *mean = g->stats[0];
+  if (max) *max = g->stats[1];
+  return GGNN_OK;
+}
+
+int ggnn_graph_import_dnn(ggnn_graph* g, const float* dnn1_host, float mean, float max) {
+  if (!g) return fail(GGNN_ERR_INVALID, "graph is NULL");
+  if (!(mean >= 0.0f) || !(max >= 0.0f)) return fail(GGNN_ERR_INVALID, "statistics must not be negative");
+  HIP_TRY(hipStreamSynchronize(g->stream));
+  if (dnn1_host) HIP_TRY(hipMemcpy(g->dnn1, dnn1_host, sizeof(float) * g->N, hipMemcpyHostToDevice));
+  g->stats[0] = mean;
+  g->stats[1] = max;
+  return GGNN_OK;
+}
+
+int ggnn_graph_export_inv_count(const ggnn_graph* g, int32_t layer, int32_t* count_host) {
+  if (!g || !count_host) return fail(GGNN_ERR_INVALID, "NULL argument");
+  if (layer < 0 || layer >= g->L) return fail(GGNN_ERR_INVALID, "layer %d outside [0, %d)", layer, g->L);
+  HIP_TRY(hipStreamSynchronize(g->stream));
+  HIP_TRY(hipMemcpy(count_host, g->inv_count[layer], sizeof(int32_t) * g->n[layer], hipMemcpyDeviceToHost));
+  return GGNN_OK;
+}
+
+}  // extern "C"

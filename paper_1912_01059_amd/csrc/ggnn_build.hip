@@ -1,0 +1,318 @@
+// Construction kernels other than the searches: top-layer selection (Sec. 4.1), the two
+// first-neighbour statistics (Eq. 3, Eq. 4), granting and applying inverse links (Alg. 5).
+#include "ggnn_launch.h"
+
+namespace ggnn {
+
+__global__ void fill_i32_kernel(int32_t* p, int64_t n, int32_t v) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) p[i] = v;
+}
+hipError_t launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t stream) {
+  if (n <= 0) return hipSuccess;
+  int64_t blocks = (n + 255) / 256;
+  if (blocks > 65536) blocks = 65536;
+  fill_i32_kernel<<<(unsigned)blocks, 256, 0, stream>>>(p, n, v);
+  return hipGetLastError();
+}
+
+// unit-length float32 copy of the base rows (cosine): x / sqrt(sum x^2), the sum taken in
+// the fixed order of every distance; 8 lanes per row
+__global__ __launch_bounds__(kWave) void normalise_kernel(const uint8_t* __restrict__ base, int dtype, int64_t N,
+                                                          int D, float* __restrict__ out) {
+  const int lane = threadIdx.x, sub = lane & (kRowLanes - 1), grp = lane / kRowLanes;
+  const int64_t row = (int64_t)blockIdx.x * kRowsPerPass + grp;
+  const bool act = row < N;
+  const int per = (dtype == 1) ? 16 : 4;
+  const int nchunks = (D + per - 1) / per;
+  float acc = 0.0f;
+  if (act) {
+    for (int chunk = sub; chunk < nchunks; chunk += kRowLanes) {
+      for (int e = 0; e < per; e++) {
+        int j = chunk * per + e;
+        if (j >= D) break;
+        float x = (dtype == 1) ? (float)base[(size_t)row * D + j] : ((const float*)base)[(size_t)row * D + j];
+        acc = __builtin_fmaf(x, x, acc);
+      }
+    }
+  }
+  acc = row_reduce(acc);
+  const float nrm = __builtin_sqrtf(acc);
+  if (act) {
+    for (int chunk = sub; chunk < nchunks; chunk += kRowLanes) {
+      for (int e = 0; e < per; e++) {
+        int j = chunk * per + e;
+        if (j >= D) break;
+        float x = (dtype == 1) ? (float)base[(size_t)row * D + j] : ((const float*)base)[(size_t)row * D + j];
+        out[(size_t)row * D + j] = (nrm > 0.0f) ? x / nrm : x;
+      }
+    }
+  }
+}
+hipError_t launch_normalise(const void* base, int dtype, int64_t N, int D, float* out, hipStream_t stream) {
+  const int64_t blocks = (N + kRowsPerPass - 1) / kRowsPerPass;
+  normalise_kernel<<<(unsigned)blocks, kWave, 0, stream>>>((const uint8_t*)base, dtype, N, D, out);
+  return hipGetLastError();
+}
+
+// Sec. 4.1 Select: one wavefront per child segment.  Child j of a parent supplies
+// floor((j+1)s/g) - floor(js/g) of the parent's s points: the members with the largest
+// Efraimidis-Spirakis key log(u)/w, w = d_nn1, ties towards the smaller id.
+__device__ inline double select_uniform(uint64_t seed, int l_top, int64_t row) {
+  uint64_t x = mix64(seed ^ mix64(((uint64_t)l_top << 56) + (uint64_t)row + 0x632BE59BD9B4E019ull));
+  return ((double)(x >> 12) + 0.5) * (1.0 / 4503599627370496.0);
+}
+__global__ __launch_bounds__(kWave) void select_kernel(GraphDev G, int l_top, const float* __restrict__ dnn1,
+                                                       int32_t* __restrict__ to_lower, int32_t* __restrict__ to_base) {
+  __shared__ double key[kWave];
+  __shared__ int32_t mem[kWave];
+  const int lane = threadIdx.x;
+  const int lc = l_top - 1;
+  const int64_t child = blockIdx.x;
+  const int64_t t = child / G.g;
+  const int j = (int)(child % G.g);
+  const int share = (int)(((int64_t)(j + 1) * G.s) / G.g - ((int64_t)j * G.s) / G.g);
+  if (share == 0) return;
+  const int offset = (int)(((int64_t)j * G.s) / G.g);
+  int cnt;
+  int32_t m = -1;
+  if (lc == 0) {
+    int64_t lo = seg0_lo(G, child), hi = seg0_lo(G, child + 1);
+    cnt = (int)(hi - lo);
+    if (lane < cnt) m = (int32_t)perm_fwd(G, lo + lane);
+  } else {
+    cnt = G.s;
+    if (lane < cnt) m = (int32_t)(child * G.s + lane);
+  }
+  int32_t row = -1;
+  double kv = 0.0;
+  if (lane < cnt) {
+    row = (lc == 0) ? m : G.to_base[lc][m];
+    double w = (double)dnn1[row];
+    kv = (w > 0.0) ? log(select_uniform(G.seed, l_top, row)) / w : -INFINITY;
+  }
+  key[lane] = kv;
+  mem[lane] = m;
+  __syncthreads();
+  if (lane < cnt) {
+    int rank = 0;
+    for (int i = 0; i < cnt; i++) rank += (key[i] > kv) || (key[i] == kv && mem[i] < m);
+    if (rank < share) {
+      to_lower[t * G.s + offset + rank] = m;
+      to_base[t * G.s + offset + rank] = row;
+    }
+  }
+}
+hipError_t launch_select(const GraphDev& G, int l_top, const float* dnn1, int32_t* to_lower, int32_t* to_base,
+                         hipStream_t stream) {
+  const int64_t children = G.n[l_top] / G.s * G.g;
+  select_kernel<<<(unsigned)children, kWave, 0, stream>>>(G, l_top, dnn1, to_lower, to_base);
+  return hipGetLastError();
+}
+
+// Sec. 4.1 Stats: mean and maximum of d_nn1 over the bottom layer.  Two fixed-shape stages
+// (float64 partial sums per block, then one block), so the result is reproducible.
+constexpr int kStatBlocks = 1024;
+__global__ __launch_bounds__(256) void stats_stage1(const float* __restrict__ x, int64_t n, double* __restrict__ partial) {
+  __shared__ double ssum[256];
+  __shared__ double smax[256];
+  const int64_t per = (n + kStatBlocks - 1) / kStatBlocks;
+  const int64_t lo = (int64_t)blockIdx.x * per;
+  const int64_t hi = lo + per < n ? lo + per : n;
+  double s = 0.0, m = 0.0;
+  for (int64_t i = lo + threadIdx.x; i < hi; i += 256) {
+    double v = (double)x[i];
+    s += v;
+    m = v > m ? v : m;
+  }
+  ssum[threadIdx.x] = s;
+  smax[threadIdx.x] = m;
+  __syncthreads();
+  for (int w = 128; w >= 1; w >>= 1) {
+    if ((int)threadIdx.x < w) {
+      ssum[threadIdx.x] += ssum[threadIdx.x + w];
+      smax[threadIdx.x] = smax[threadIdx.x] > smax[threadIdx.x + w] ? smax[threadIdx.x] : smax[threadIdx.x + w];
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    partial[blockIdx.x] = ssum[0];
+    partial[kStatBlocks + blockIdx.x] = smax[0];
+  }
+}
+__global__ __launch_bounds__(kStatBlocks) void stats_stage2(const double* __restrict__ partial, int64_t n, float* __restrict__ out) {
+  __shared__ double ssum[kStatBlocks];
+  __shared__ double smax[kStatBlocks];
+  ssum[threadIdx.x] = partial[threadIdx.x];
+  smax[threadIdx.x] = partial[kStatBlocks + threadIdx.x];
+  __syncthreads();
+  for (int w = kStatBlocks / 2; w >= 1; w >>= 1) {
+    if ((int)threadIdx.x < w) {
+      ssum[threadIdx.x] += ssum[threadIdx.x + w];
+      smax[threadIdx.x] = smax[threadIdx.x] > smax[threadIdx.x + w] ? smax[threadIdx.x] : smax[threadIdx.x + w];
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    out[0] = (float)(ssum[0] / (double)n);
+    out[1] = (float)smax[0];
+  }
+}
+hipError_t launch_stats(const float* x, int64_t n, double* partial, float* out, hipStream_t stream) {
+  stats_stage1<<<kStatBlocks, 256, 0, stream>>>(x, n, partial);
+  stats_stage2<<<1, kStatBlocks, 0, stream>>>(partial, n, out);
+  return hipGetLastError();
+}
+
+// ---- granting inverse links (Alg. 5, last loop) -----------------------------------------
+// The paper lets atomics decide which request gets a free slot of a row.  Here the slots of
+// a row go to the requests with the smallest (distance, z); a request that loses moves on to
+// its next candidate.  Repeating propose / resolve until no request is left proposing gives
+// the same links whatever the order in which the hardware runs the threads.
+
+__device__ inline bool row_has(const int32_t* row, int n, int32_t id) {
+  for (int i = 0; i < n; i++)
+    if (row[i] == id) return true;
+  return false;
+}
+
+__global__ void sym_propose_kernel(GraphDev G, int layer, SymBuffers sb, int B, int first) {
+  const int64_t z = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (z >= G.n[layer]) return;
+  const int knn = G.K / 2, ksym = G.K - knn;
+  if (first) {
+    sb.ptr[z] = 0;
+    sb.state[z] = sb.npref[z] > 0 ? 1 : 0;
+  }
+  if (sb.state[z] != 1) return;
+  const int np = sb.npref[z];
+  int ptr = sb.ptr[z];
+  const int32_t* __restrict__ Ed = G.edges[layer];
+  int32_t cand = -1;
+  for (; ptr < np; ptr++) {
+    cand = key_id(sb.pref[(size_t)z * B + ptr]);
+    const int ni = sb.ninv[cand];
+    if (ksym - ni > 0 && cand != (int32_t)z && !row_has(Ed + (size_t)cand * G.K, knn, (int32_t)z) &&
+        !row_has(sb.inv + (size_t)cand * ksym, ni, (int32_t)z))
+      break;
+  }
+  sb.ptr[z] = ptr;
+  if (ptr >= np) {
+    sb.state[z] = 0;  // no candidate with a free slot: the link is dropped
+    return;
+  }
+  sb.next[z] = atomicExch(&sb.head[cand], (int32_t)z);
+}
+
+__device__ inline u64 request_key(const SymBuffers& sb, int B, int32_t r) {
+  u64 k = sb.pref[(size_t)r * B + sb.ptr[r]];
+  return (k & 0xFFFFFFFF00000000ull) | (uint32_t)r;  // (distance to the request's midpoint, z)
+}
+
+__global__ void sym_resolve_kernel(GraphDev G, int layer, SymBuffers sb, int B) {
+  const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (p >= G.n[layer]) return;
+  int32_t r = sb.head[p];
+  if (r < 0) return;
+  sb.head[p] = -1;
+  const int knn = G.K / 2, ksym = G.K - knn;
+  const int cap = ksym - sb.ninv[p];
+  int32_t* H = sb.hold + (size_t)p * ksym;  // kept ascending by request_key
+  int nh = sb.nhold[p];
+  int losers = 0;
+  while (r >= 0) {
+    const int32_t nxt = sb.next[r];
+    const u64 kr = request_key(sb, B, r);
+    int32_t out = -1;
+    if (nh < cap) {
+      int pos = nh++;
+      while (pos > 0 && request_key(sb, B, H[pos - 1]) > kr) { H[pos] = H[pos - 1]; pos--; }
+      H[pos] = r;
+      sb.state[r] = 2;
+    } else if (request_key(sb, B, H[nh - 1]) > kr) {
+      out = H[nh - 1];
+      int pos = nh - 1;
+      while (pos > 0 && request_key(sb, B, H[pos - 1]) > kr) { H[pos] = H[pos - 1]; pos--; }
+      H[pos] = r;
+      sb.state[r] = 2;
+    } else {
+      out = r;
+    }
+    if (out >= 0) {
+      sb.state[out] = 1;
+      sb.ptr[out] = sb.ptr[out] + 1;
+      losers++;
+    }
+    r = nxt;
+  }
+  sb.nhold[p] = nh;
+  if (losers) atomicAdd(sb.pending, losers);
+}
+
+__global__ void sym_commit_kernel(GraphDev G, int layer, SymBuffers sb) {
+  const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (p >= G.n[layer]) return;
+  const int knn = G.K / 2, ksym = G.K - knn;
+  const int nh = sb.nhold[p];
+  int ni = sb.ninv[p];
+  for (int i = 0; i < nh; i++) sb.inv[(size_t)p * ksym + ni++] = sb.hold[(size_t)p * ksym + i];
+  sb.ninv[p] = ni;
+  sb.nhold[p] = 0;
+}
+
+// Sec. 4.2: a row keeps at least k_nn true neighbours, its inverse links replace the
+// farthest ones; a link that repeats a kept neighbour is dropped (until stable).
+__global__ void sym_apply_kernel(GraphDev G, int layer, SymBuffers sb, int32_t* __restrict__ edges,
+                                 int32_t* __restrict__ inv_count) {
+  const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (p >= G.n[layer]) return;
+  const int K = G.K, knn = K / 2, ksym = K - knn;
+  int32_t* row = edges + (size_t)p * K;
+  const int32_t* links = sb.inv + (size_t)p * ksym;
+  const int ni = sb.ninv[p];
+  int valid = 0;
+  while (valid < K && row[valid] >= 0) valid++;
+  int nl = ni, keep;
+  for (;;) {
+    keep = valid < K - nl ? valid : K - nl;
+    int m = 0;
+    for (int i = 0; i < ni; i++) m += !row_has(row, keep, links[i]);
+    if (m == nl) break;
+    nl = m;
+  }
+  int o = keep;
+  for (int i = 0; i < ni; i++)
+    if (!row_has(row, keep, links[i])) row[o++] = links[i];
+  for (; o < K; o++) row[o] = -1;
+  inv_count[p] = nl;
+}
+
+static inline unsigned blocks_for(int64_t n) { return (unsigned)((n + 255) / 256); }
+
+hipError_t launch_sym_propose(const GraphDev& G, int layer, const SymBuffers& sb, int B, hipStream_t stream);
+hipError_t launch_sym_propose_impl(const GraphDev& G, int layer, const SymBuffers& sb, int B, int first, hipStream_t stream) {
+  sym_propose_kernel<<<blocks_for(G.n[layer]), 256, 0, stream>>>(G, layer, sb, B, first);
+  return hipGetLastError();
+}
+hipError_t launch_sym_propose(const GraphDev& G, int layer, const SymBuffers& sb, int B, hipStream_t stream) {
+  return launch_sym_propose_impl(G, layer, sb, B, 0, stream);
+}
+hipError_t launch_sym_propose_first(const GraphDev& G, int layer, const SymBuffers& sb, int B, hipStream_t stream) {
+  return launch_sym_propose_impl(G, layer, sb, B, 1, stream);
+}
+hipError_t launch_sym_resolve(const GraphDev& G, int layer, const SymBuffers& sb, int B, hipStream_t stream) {
+  sym_resolve_kernel<<<blocks_for(G.n[layer]), 256, 0, stream>>>(G, layer, sb, B);
+  return hipGetLastError();
+}
+hipError_t launch_sym_commit(const GraphDev& G, int layer, const SymBuffers& sb, hipStream_t stream) {
+  sym_commit_kernel<<<blocks_for(G.n[layer]), 256, 0, stream>>>(G, layer, sb);
+  return hipGetLastError();
+}
+hipError_t launch_sym_apply(const GraphDev& G, int layer, const SymBuffers& sb, int32_t* edges, int32_t* inv_count,
+                            hipStream_t stream) {
+  sym_apply_kernel<<<blocks_for(G.n[layer]), 256, 0, stream>>>(G, layer, sb, edges, inv_count);
+  return hipGetLastError();
+}
+
+}  // namespace ggnn

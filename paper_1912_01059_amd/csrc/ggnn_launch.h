@@ -1,0 +1,48 @@
+// Host-side launchers shared by the API translation unit and the kernel translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ggnn_device.h"
+
+namespace ggnn {
+
+// state of one symmetric-linking pass over a layer (device buffers owned by the graph)
+struct SymBuffers {
+  int32_t* inv;       // n x ksym inverse links granted so far
+  int32_t* ninv;      // n
+  u64* pref;          // n x B candidate keys of the failed searches of the current round
+  int32_t* npref;     // n
+  int32_t* ptr;       // n  index of the candidate a request currently proposes to
+  int32_t* state;     // n  0 = no request / settled nowhere, 1 = proposing, 2 = holds a slot
+  int32_t* hold;      // n x ksym requests (their z) holding a slot of this row in this round
+  int32_t* nhold;     // n
+  int32_t* head;      // n  head of the list of requests proposing to this row
+  int32_t* next;      // n  links of those lists
+  int32_t* pending;   // 1  number of requests that still have to propose
+};
+
+// search kernels (ggnn_search.hip)
+hipError_t launch_query(const GraphDev& G, int dtype, int metric, const void* queries, int64_t Q, int k,
+                        const SearchParams& sp, int every_layer, int32_t* ids, float* dists, uint32_t* counters,
+                        hipStream_t stream);
+hipError_t launch_merge(const GraphDev& G, int dtype, int metric, int l_top, int l_m, const SearchParams& sp,
+                        int32_t* out_rows, float* dnn1, hipStream_t stream);
+hipError_t launch_sym_search(const GraphDev& G, int dtype, int metric, int layer, int round, float w_mid,
+                             const SearchParams& sp, const SymBuffers& sb, hipStream_t stream);
+
+// construction kernels (ggnn_build.hip)
+hipError_t launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t stream);
+hipError_t launch_normalise(const void* base, int dtype, int64_t N, int D, float* out, hipStream_t stream);
+hipError_t launch_select(const GraphDev& G, int l_top, const float* dnn1, int32_t* to_lower, int32_t* to_base,
+                         hipStream_t stream);
+// mean / max of x[0..n): partial holds 2*1024 doubles of scratch, out[0] = mean, out[1] = max
+hipError_t launch_stats(const float* x, int64_t n, double* partial, float* out, hipStream_t stream);
+hipError_t launch_sym_propose_first(const GraphDev& G, int layer, const SymBuffers& sb, int B, hipStream_t stream);
+hipError_t launch_sym_propose(const GraphDev& G, int layer, const SymBuffers& sb, int B, hipStream_t stream);
+hipError_t launch_sym_resolve(const GraphDev& G, int layer, const SymBuffers& sb, int B, hipStream_t stream);
+hipError_t launch_sym_commit(const GraphDev& G, int layer, const SymBuffers& sb, hipStream_t stream);
+hipError_t launch_sym_apply(const GraphDev& G, int layer, const SymBuffers& sb, int32_t* edges, int32_t* inv_count,
+                            hipStream_t stream);
+
+}  // namespace ggnn

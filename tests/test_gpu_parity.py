@@ -1,0 +1,253 @@
+"""GPU parity tests: the HIP library against the CPU oracle, element by element, through the C ABI."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+
+
+@pytest.fixture(scope="module")
+def ggnn():
+    _need_gpu()
+    import paper_1912_01059_amd as m
+    m.lib()
+    return m
+
+
+@pytest.fixture(scope="module")
+def R():
+    from oracle import ggnn_ref
+    return ggnn_ref
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def to_gpu_graph(ggnn, og, base_t, **kw):
+    """Loads the state of an oracle graph into a library graph over the same base."""
+    g = ggnn.graph_create(base_t, og.K, og.L, seed=og.seed, metric=og.metric, segment_size=og.s, **kw)
+    for l in range(og.L):
+        g.import_layer(l, og.edges(l), og.to_lower(l) if l >= 1 else None, og.to_base(l) if l >= 1 else None)
+    st = og.stats()
+    g.import_dnn(og.dnn1(), float(st[0]), float(st[1]))
+    return g
+
+
+def assert_same_results(got_ids, got_d, want_ids, want_d):
+    got_ids, got_d = got_ids.cpu().numpy(), got_d.cpu().numpy()
+    assert np.array_equal(got_ids, want_ids)
+    assert np.array_equal(got_d.view(np.uint32), want_d.view(np.uint32))  # bit for bit
+
+
+# ------------------------------------------------------------------------------ query
+
+@pytest.mark.parametrize("every_layer", [False, True])
+@pytest.mark.parametrize("k,beam,tau", [(10, 10, 0.0), (10, 10, 0.3), (10, 64, 0.5), (1, 10, 0.4), (24, 24, 0.2)])
+def test_query_matches_oracle_on_config1(ggnn, R, sift10k, sift10k_oracle_graph, every_layer, k, beam, tau):
+    base, queries, cfg = sift10k
+    og = sift10k_oracle_graph
+    g = to_gpu_graph(ggnn, og, dev(base))
+    ids, d, cnt = g.query(dev(queries), k, beam, tau, every_layer=every_layer, counters=True)
+    rids, rd, rcnt = og.query(queries, k, beam, tau, every_layer=every_layer, counters=True)
+    assert_same_results(ids, d, rids, rd)
+    assert np.array_equal(cnt.cpu().numpy().astype(np.uint32), rcnt)
+
+
+def test_query_small_capacities_and_iteration_limit(ggnn, R, sift10k, sift10k_oracle_graph):
+    """prioq overflow, visited limit and iteration limit behave as in the oracle."""
+    base, queries, cfg = sift10k
+    og = sift10k_oracle_graph
+    g = to_gpu_graph(ggnn, og, dev(base))
+    q = dev(queries[:300])
+    for P, V, it in [(4, 16, 16), (8, 64, 10), (100, 500, 500), (64, 384, 1)]:
+        ids, d, cnt = g.query(q, 10, 10, 0.4, pq_cap=P, visited_cap=V, max_iter=it, every_layer=True, counters=True)
+        rids, rd, rcnt = og.query(queries[:300], 10, 10, 0.4, pq_cap=P, visited_cap=V, max_iter=it, every_layer=True,
+                                  counters=True)
+        assert_same_results(ids, d, rids, rd)
+        assert np.array_equal(cnt.cpu().numpy().astype(np.uint32), rcnt)
+
+
+def test_query_exhaustive_beam_equals_brute_force(ggnn, R):
+    """best as long as the data set: the whole reachable set is visited; on a connected graph
+    that is the exact answer."""
+    rng = np.random.default_rng(5)
+    N, D, K = 200, 16, 12
+    base = rng.standard_normal((N, D)).astype(np.float32)
+    og = R.Graph(base, K, 2, seed=3).build()
+    g = to_gpu_graph(ggnn, og, dev(base))
+    q = rng.standard_normal((64, D)).astype(np.float32)
+    ids, d = g.query(dev(q), 10, N, 0.0, pq_cap=N, visited_cap=N, max_iter=N)
+    rids, rd = og.query(q, 10, N, 0.0, pq_cap=N, visited_cap=N, max_iter=N)
+    assert_same_results(ids, d, rids, rd)
+    gt_ids, gt_d = R.bruteforce(base, q, 10)
+    assert np.array_equal(ids.cpu().numpy(), gt_ids)
+
+
+def test_query_real_valued_data_bit_exact(ggnn, R):
+    """Real-valued rows (D=96, unit length): the fixed float32 summation order makes the
+    traversal identical to the oracle's, not merely close."""
+    import ggnn_inputs
+    base, queries, cfg = ggnn_inputs.make("deep1m", n=6000, q=400)
+    og = R.Graph(base, 24, 3, seed=9).build()
+    g = to_gpu_graph(ggnn, og, dev(base))
+    for every_layer in (False, True):
+        ids, d, cnt = g.query(dev(queries), 10, 10, 0.4, every_layer=every_layer, counters=True)
+        rids, rd, rcnt = og.query(queries, 10, 10, 0.4, every_layer=every_layer, counters=True)
+        assert_same_results(ids, d, rids, rd)
+        assert np.array_equal(cnt.cpu().numpy().astype(np.uint32), rcnt)
+    # and within 1e-5 relative of float64 distances
+    b64, q64 = base.astype(np.float64), queries.astype(np.float64)
+    got = ids.cpu().numpy()
+    for i in range(0, 400, 13):
+        ref = np.sqrt(((b64[got[i]] - q64[i]) ** 2).sum(1))
+        assert np.allclose(d.cpu().numpy()[i], ref, rtol=1e-5, atol=0)
+
+
+def test_query_cosine_matches_oracle(ggnn, R):
+    import ggnn_inputs
+    base, queries, cfg = ggnn_inputs.make("glove1m", n=5000, q=300)
+    og = R.Graph(base, 40, 3, metric=R.COSINE, seed=4).build()
+    g = to_gpu_graph(ggnn, og, dev(base))
+    ids, d = g.query(dev(queries), 10, 10, 0.5, visited_cap=512, every_layer=True)
+    rids, rd = og.query(queries, 10, 10, 0.5, visited_cap=512, every_layer=True)
+    assert_same_results(ids, d, rids, rd)
+
+
+def test_query_uint8_matches_oracle(ggnn, R):
+    import ggnn_inputs
+    base, queries, cfg = ggnn_inputs.make("sift100m_u8", n=5000, q=300)
+    assert base.dtype == np.uint8
+    og = R.Graph(base, 24, 3, seed=4).build()
+    g = to_gpu_graph(ggnn, og, dev(base))
+    ids, d = g.query(dev(queries), 10, 10, 0.3, every_layer=True)
+    rids, rd = og.query(queries, 10, 10, 0.3, every_layer=True)
+    assert_same_results(ids, d, rids, rd)
+
+
+def test_query_edge_cases(ggnn, R, sift10k, sift10k_oracle_graph):
+    base, queries, cfg = sift10k
+    og = sift10k_oracle_graph
+    g = to_gpu_graph(ggnn, og, dev(base))
+    # no queries
+    ids, d = g.query(dev(queries[:0]), 10, 10, 0.3)
+    assert ids.shape == (0, 10)
+    # one query, ragged sizes
+    for Q in (1, 63, 65):
+        ids, d = g.query(dev(queries[:Q]), 10, 10, 0.3)
+        rids, rd = og.query(queries[:Q], 10, 10, 0.3)
+        assert_same_results(ids, d, rids, rd)
+    # invalid arguments are errors, not faults
+    with pytest.raises(ggnn.GgnnError):
+        g.query(dev(queries[:4]), 0, 10, 0.3)
+    with pytest.raises(ggnn.GgnnError):
+        g.query(dev(queries[:4]), 10, 10, -1.0)
+    with pytest.raises(ggnn.GgnnError):
+        g.query(dev(queries[:4]), 10, 10, 0.3, visited_cap=100, max_iter=200)
+    with pytest.raises(ggnn.GgnnError):
+        g.query(dev(queries[:4]), 10, 4000, 0.3, pq_cap=4000, visited_cap=4000)  # over the LDS budget
+    bad = og.edges(0).copy()
+    bad[5, 3] = bad[5, 2]
+    with pytest.raises(ggnn.GgnnError):
+        g.import_layer(0, bad)
+    bad = og.edges(0).copy()
+    bad[7, 0] = 10_000
+    with pytest.raises(ggnn.GgnnError):
+        g.import_layer(0, bad)
+
+
+# ------------------------------------------------------------------------------ construction steps
+
+def test_merge_select_stats_match_oracle_step_by_step(ggnn, R, sift10k):
+    """Every deterministic construction step, run on the state the oracle reached so far."""
+    base, _, cfg = sift10k
+    K, L = cfg["K"], cfg["levels"]
+    og = R.Graph(base, K, L, seed=42)
+    g = ggnn.graph_create(dev(base), K, L, seed=42)
+    assert g.n == og.n and g.g == og.g
+    p = R.default_params()
+
+    def sync_from_oracle():
+        for l in range(L):
+            e = og.edges(l)
+            if (e >= 0).any() or l == 0:
+                g.import_layer(l, e, og.to_lower(l) if l >= 1 else None, og.to_base(l) if l >= 1 else None)
+        st = og.stats()
+        g.import_dnn(og.dnn1(), float(st[0]), float(st[1]))
+
+    def check_layer(l):
+        e, tl, tb = g.export_layer(l)
+        assert np.array_equal(e, og.edges(l)), "edges of layer %d" % l
+        if l >= 1:
+            assert np.array_equal(tl, og.to_lower(l)) and np.array_equal(tb, og.to_base(l))
+
+    def check_dnn():
+        d, mean, mx = g.export_dnn()
+        assert np.array_equal(d.view(np.uint32), og.dnn1().view(np.uint32))
+        assert mx == og.stats()[1]
+        assert abs(mean - og.stats()[0]) <= 2 ** -22 * mean
+
+    # merge(0,0): exhaustive search inside the bottom segments, then stats
+    og.merge(0, 0, p); g.merge(0, 0); check_layer(0); check_dnn()
+    og.sym(0, p); sync_from_oracle()
+    for l_top in range(1, L):
+        og.select(l_top); g.select(l_top)
+        e, tl, tb = g.export_layer(l_top)
+        assert np.array_equal(tl, og.to_lower(l_top)) and np.array_equal(tb, og.to_base(l_top))
+        for l_m in range(l_top, -1, -1):
+            og.merge(l_top, l_m, p); g.merge(l_top, l_m); check_layer(l_m)
+            if l_m == 0:
+                check_dnn()
+            og.sym(l_m, p); sync_from_oracle()
+
+
+def test_sym_matches_oracle(ggnn, R, sift10k):
+    base, _, cfg = sift10k
+    K, L = cfg["K"], cfg["levels"]
+    og = R.Graph(base, K, L, seed=42)
+    g = ggnn.graph_create(dev(base), K, L, seed=42)
+    p = R.default_params()
+    og.merge(0, 0, p)
+    g.import_layer(0, og.edges(0))
+    st = og.stats()
+    g.import_dnn(og.dnn1(), float(st[0]), float(st[1]))
+    og.sym(0, p)
+    g.sym(0)
+    e, _, _ = g.export_layer(0)
+    assert np.array_equal(g.export_inv_count(0), og.inv_count(0))
+    assert np.array_equal(e, og.edges(0))
+
+
+def test_full_build_matches_oracle(ggnn, R, sift10k, sift10k_oracle_graph):
+    """The whole construction on config 1 gives the oracle's graph, layer by layer."""
+    base, queries, cfg = sift10k
+    og = sift10k_oracle_graph
+    g = ggnn.build(dev(base), cfg["K"], cfg["levels"], seed=42)
+    for l in range(g.L):
+        e, tl, tb = g.export_layer(l)
+        assert np.array_equal(e, og.edges(l)), "layer %d" % l
+        if l >= 1:
+            assert np.array_equal(tl, og.to_lower(l)) and np.array_equal(tb, og.to_base(l))
+    t = g.times()
+    assert t["total_ms"] > 0 and t["merge_ms"] > 0 and t["sym_ms"] > 0
+
+
+def test_build_quality_and_recall(ggnn, R, sift10k, sift10k_gt):
+    """Invariants of a GPU-built graph and recall against exhaustive search (config 1)."""
+    base, queries, cfg = sift10k
+    K = cfg["K"]
+    g = ggnn.build(dev(base), K, cfg["levels"], seed=7)
+    e0, _, _ = g.export_layer(0)
+    assert (e0 >= 0).all()
+    srt = np.sort(e0, axis=1)
+    assert (np.diff(srt, axis=1) > 0).all()                      # distinct
+    assert not (e0 == np.arange(len(e0))[:, None]).any()         # no self loop
+    assert g.export_inv_count(0).max() <= K - K // 2
+    ids, _ = g.query(dev(queries), 10, 10, 0.3, every_layer=True)
+    assert R.recall(ids.cpu().numpy(), sift10k_gt[0]) >= 0.99
