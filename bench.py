@@ -1,0 +1,196 @@
+#!/usr/bin/env python3
+"""Benchmark of the GGNN hot path on one MI355X.
+
+Workload: the 1M x 128 configuration (float32 integer-valued vectors in [0,255] from a seeded
+1024-component Gaussian mixture, 10 000 queries of the same distribution, L2, K=24, k=10).
+The graph is built once on the GPU (build seconds are reported); a "step" is one search of the
+whole query batch at the operating point that first reaches Recall@10 >= 0.95.  Prints one
+JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def ground_truth(torch, base, queries, k, chunk=500):
+    """Exact k nearest neighbours by exhaustive search with torch (measurement plumbing, outside
+    the timed region).  On integer-valued data every float32 partial sum is an exact integer."""
+    b = base.float()
+    bn = (b * b).sum(1)
+    ids, d = [], []
+    for lo in range(0, queries.shape[0], chunk):
+        q = queries[lo:lo + chunk].float()
+        d2 = (q * q).sum(1)[:, None] + bn[None, :] - 2.0 * (q @ b.T)
+        v, i = torch.topk(d2, k, dim=1, largest=False)
+        ids.append(i)
+        d.append(v.clamp_min(0).sqrt())
+    return torch.cat(ids), torch.cat(d)
+
+
+def recall_at_k(dists, gt_d):
+    """Recall@k (the paper's consensus C@k), tolerant of exact distance ties at the k-th place:
+    a returned point counts if it is no farther than the k-th true neighbour."""
+    k = gt_d.shape[1]
+    return float(((dists <= gt_d[:, k - 1:k]).sum(1).clamp(max=k).float().mean() / k).item())
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="sift1m")
+    ap.add_argument("--n", type=int, default=None, help="override the number of base points (debugging)")
+    ap.add_argument("--levels", type=int, default=4)
+    ap.add_argument("--slack", type=float, default=0.05, help="tau_q of the timed operating point")
+    ap.add_argument("--beam", type=int, default=10)
+    ap.add_argument("--visited-cap", type=int, default=512)
+    ap.add_argument("--pq-cap", type=int, default=64)
+    ap.add_argument("--sweep", action="store_true", help="also trace the QPS-vs-recall curve")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=2000)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the method shards by replicating the graph "
+              "or by independent per-shard graphs; see DESIGN.md); --gpus %d is not supported" % args.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import ggnn_inputs
+    import paper_1912_01059_amd as ggnn
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    base_np, queries_np, cfg = ggnn_inputs.make(args.workload, n=args.n)
+    base = torch.from_numpy(base_np).to(dev)
+    queries = torch.from_numpy(queries_np).to(dev)
+    N, D = base.shape
+    Q, k, K = queries.shape[0], cfg["k"], cfg["K"]
+    esize = base.element_size()
+    metric = ggnn.COSINE if cfg["metric"] == "cosine" else ggnn.L2
+
+    # ---- construction (timed once; the graph stays resident) ----
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    graph = ggnn.build(base, K, args.levels, seed=42, metric=metric)
+    torch.cuda.synchronize()
+    build_s = time.perf_counter() - t0
+    phases = graph.times()
+
+    gt_ids, gt_d = ground_truth(torch, base, queries, k)
+
+    # ---- operating point (found with --sweep; the default is the cheapest one that reaches
+    # Recall@10 >= 0.95 on this workload) and, on request, the QPS-vs-recall curve ----
+    ids = torch.empty((Q, k), dtype=torch.int32, device=dev)
+    dists = torch.empty((Q, k), dtype=torch.float32, device=dev)
+    chosen = dict(beam=args.beam, slack=args.slack, visited_cap=args.visited_cap, pq_cap=args.pq_cap)
+    kw = dict(pq_cap=chosen["pq_cap"], visited_cap=chosen["visited_cap"], every_layer=True)
+    curve = []
+    if args.sweep:
+        sweep = [dict(beam=10, slack=sl, visited_cap=v, pq_cap=64)
+                 for (sl, v) in [(0.02, 512), (0.035, 512), (0.05, 512), (0.065, 512), (0.08, 512), (0.1, 1024),
+                                 (0.15, 1024), (0.2, 1024), (0.3, 1024)]]
+        for op in sweep:
+            okw = dict(pq_cap=op["pq_cap"], visited_cap=op["visited_cap"], every_layer=True)
+            _, _, c = graph.query(queries, k, op["beam"], op["slack"], counters=True, out=(ids, dists), **okw)
+            rec = recall_at_k(dists, gt_d)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(3):
+                graph.query(queries, k, op["beam"], op["slack"], out=(ids, dists), asynchronous=True, **okw)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / 3
+            cm = c.double().mean(0).tolist()
+            curve.append(dict(op, recall=round(rec, 4), qps=round(Q / ms * 1e3), pops=round(cm[0], 1),
+                              dist_evals=round(cm[1], 1)))
+    _, _, cnt = graph.query(queries, k, chosen["beam"], chosen["slack"], counters=True, out=(ids, dists), **kw)
+    chosen["cnt"] = cnt
+
+    # ---- timed region: exactly `steps` searches of the whole batch ----
+    stream = torch.cuda.current_stream()
+    for _ in range(args.warmup):
+        graph.query(queries, k, chosen["beam"], chosen["slack"], out=(ids, dists), asynchronous=True, **kw)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for _ in range(args.steps):
+        graph.query(queries, k, chosen["beam"], chosen["slack"], out=(ids, dists), asynchronous=True, **kw)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    kernel_ms = e0.elapsed_time(e1) / args.steps
+    ms_per_step = wall_ms / args.steps
+    qps = Q / ms_per_step * 1e3
+    final_recall = recall_at_k(dists, gt_d)
+
+    # ---- roofline of the search kernel: algorithmic bytes per launch / kernel time ----
+    # per query: the query vector, the s start rows with their ids, one adjacency row per pop,
+    # one base row per distance evaluation, the k results (ids + distances)
+    cnt = chosen["cnt"].double().sum(0).tolist()
+    s = graph.s
+    algo_bytes = Q * (D * esize + s * (4 + D * esize) + k * 8) + cnt[0] * K * 4 + cnt[1] * D * esize
+    achieved = algo_bytes / (kernel_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None, "kernel": "query_kernel",
+                "kernel_ms": round(kernel_ms, 3), "algorithmic_bytes_per_launch": int(algo_bytes)}
+
+    # ---- CPU baseline: the oracle's search of the same graph on a sample of the queries ----
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import ggnn_ref as R
+        og = R.Graph(base_np, K, args.levels, seed=42, metric=R.COSINE if metric == ggnn.COSINE else R.L2)
+        for l in range(graph.L):
+            e, tl, tb = graph.export_layer(l)
+            og.edges(l)[:] = e
+            if l >= 1:
+                og.to_lower(l)[:] = tl
+                og.to_base(l)[:] = tb
+        _, mean, mx = graph.export_dnn()
+        og.stats()[:] = (mean, mx)
+        ns = min(args.cpu_sample, Q)
+        t0 = time.perf_counter()
+        rids, rd = og.query(queries_np[:ns], k, chosen["beam"], chosen["slack"], pq_cap=chosen["pq_cap"],
+                            visited_cap=chosen["visited_cap"], every_layer=True)
+        cpu_s = time.perf_counter() - t0
+        same = bool(np.array_equal(rids, ids[:ns].cpu().numpy()) and np.array_equal(rd, dists[:ns].cpu().numpy()))
+        cpu = {"value": round(ns / cpu_s, 1), "unit": "queries/s", "cores": R.lib().ggnn_ref_num_threads(),
+               "kind": "oracle", "sample": "first %d of the %d queries, same graph and operating point" % (ns, Q),
+               "identical_to_gpu": same}
+
+    out = {
+        "metric": "queries/s at Recall@10>=0.95 (1M x 128 L2, k=10)", "value": round(qps, 1), "unit": "queries/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32" if esize == 4 else "u8",
+        "data": "synthetic",
+        "config": {"workload": "%s: N=%d D=%d Q=%d K=%d k=%d levels=%d" % (args.workload, N, D, Q, K, k, args.levels),
+                   "beam": chosen["beam"], "slack": chosen["slack"], "pq_cap": chosen["pq_cap"],
+                   "visited_cap": chosen["visited_cap"], "descent": "every layer (Alg. 4)"},
+        "recall_at_10": round(final_recall, 4),
+        "build_seconds": round(build_s, 3),
+        "build_phases_ms": {kk: round(v, 2) for kk, v in phases.items()},
+        "graph_bytes": graph.graph_bytes,
+        "pops_per_query": round(cnt[0] / Q, 1), "dist_evals_per_query": round(cnt[1] / Q, 1),
+        "curve": curve,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
