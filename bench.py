@@ -139,11 +139,11 @@ def main():
     final_recall = recall_at_k(dists, gt_d)
 
     # ---- roofline of the search kernel: algorithmic bytes per launch / kernel time ----
-    # per query: the query vector, the s start rows with their ids, one adjacency row per pop,
-    # one base row per distance evaluation, the k results (ids + distances)
+    # per query: the query vector, one adjacency row per pop, one base row (and its id) per row
+    # actually gathered (start points included), the k results (ids + distances)
     cnt = chosen["cnt"].double().sum(0).tolist()
     s = graph.s
-    algo_bytes = Q * (D * esize + s * (4 + D * esize) + k * 8) + cnt[0] * K * 4 + cnt[1] * D * esize
+    algo_bytes = Q * (D * esize + k * 8) + cnt[0] * K * 4 + cnt[2] * (4 + D * esize)
     achieved = algo_bytes / (kernel_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None, "kernel": "query_kernel",
@@ -185,6 +185,7 @@ def main():
         "build_phases_ms": {kk: round(v, 2) for kk, v in phases.items()},
         "graph_bytes": graph.graph_bytes,
         "pops_per_query": round(cnt[0] / Q, 1), "dist_evals_per_query": round(cnt[1] / Q, 1),
+        "rows_gathered_per_query": round(cnt[2] / Q, 1),
         "curve": curve,
         "roofline": roofline,
         "cpu_baseline": cpu,

@@ -128,7 +128,9 @@ int ggnn_query(const ggnn_graph* g, const void* queries_dev, int64_t Q, int32_t 
  * max_iter: iteration limit per layer, must be <= visited_cap so that visited never
  * forgets a point.  every_layer: 0 = Sec. 4.4 shortcut, 1 = search every layer on the way
  * down (Alg. 4).  stream: hipStream_t (NULL = the graph's stream).  counters_dev:
- * optional Q x 2 uint32 (device): pops and distance evaluations per query.
+ * optional Q x 4 uint32 (device), per query: pops; distance evaluations of the method (Alg. 2
+ * Fetch: a point counts again each time it is proposed while unknown to the cache); base rows
+ * actually gathered (fewer when re-evaluations of rejected points are skipped); 0.
  * asynchronous != 0 returns right after the launch (no synchronisation). */
 int ggnn_query_ex(const ggnn_graph* g, const void* queries_dev, int64_t Q, int32_t k, int32_t beam, float slack,
                   int32_t pq_cap, int32_t visited_cap, int32_t max_iter, int32_t every_layer, void* stream,
@@ -153,6 +155,10 @@ int ggnn_graph_export_dnn(const ggnn_graph* g, float* dnn1_host, float* mean, fl
 int ggnn_graph_import_dnn(ggnn_graph* g, const float* dnn1_host, float mean, float max);
 /* number of inverse links each row of `layer` holds after the last ggnn_sym (host, n[layer]) */
 int ggnn_graph_export_inv_count(const ggnn_graph* g, int32_t layer, int32_t* count_host);
+
+/* Where best and prioq live during a search: 0 (default) in registers whenever both hold at most
+ * 64 entries, otherwise in LDS; 1 always in LDS.  Results do not depend on it.  Process-wide. */
+int ggnn_set_cache_mode(int32_t mode);
 
 void ggnn_free(ggnn_graph* g);
 const char* ggnn_last_error(void);

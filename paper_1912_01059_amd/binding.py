@@ -45,7 +45,7 @@ EXPORTS = [
     "ggnn_build", "ggnn_build_ex", "ggnn_graph_create", "ggnn_select", "ggnn_merge", "ggnn_sym",
     "ggnn_build_steps", "ggnn_build_get_times", "ggnn_query", "ggnn_query_ex", "ggnn_graph_info",
     "ggnn_graph_export", "ggnn_graph_import", "ggnn_graph_export_dnn", "ggnn_graph_import_dnn",
-    "ggnn_graph_export_inv_count", "ggnn_free", "ggnn_last_error",
+    "ggnn_graph_export_inv_count", "ggnn_set_cache_mode", "ggnn_free", "ggnn_last_error",
 ]
 
 
@@ -74,11 +74,17 @@ def lib():
         L.ggnn_graph_export_dnn.argtypes = [vp, vp, C.POINTER(f32), C.POINTER(f32)]
         L.ggnn_graph_import_dnn.argtypes = [vp, vp, f32, f32]
         L.ggnn_graph_export_inv_count.argtypes = [vp, i32, vp]
+        L.ggnn_set_cache_mode.argtypes = [i32]
         L.ggnn_free.argtypes = [vp]
         L.ggnn_free.restype = None
         L.ggnn_last_error.restype = C.c_char_p
         _lib = L
     return _lib
+
+
+def set_cache_mode(mode: int) -> None:
+    """0: best / prioq in registers when they fit (default); 1: always in LDS."""
+    _check(lib().ggnn_set_cache_mode(mode))
 
 
 def last_error() -> str:
@@ -229,7 +235,7 @@ def query(graph, queries, k, beam, slack, pq_cap=0, visited_cap=0, max_iter=0, e
         dists = torch.empty((Q, k), dtype=torch.float32, device=queries.device)
     else:
         ids, dists = out
-    cnt = torch.zeros((Q, 2), dtype=torch.int32, device=queries.device) if counters else None
+    cnt = torch.zeros((Q, 4), dtype=torch.int32, device=queries.device) if counters else None
     if stream is None:
         stream = torch.cuda.current_stream().cuda_stream
     _check(lib().ggnn_query_ex(graph.h, _dev_ptr(queries), Q, k, beam, slack, pq_cap, visited_cap, max_iter,

@@ -10,6 +10,7 @@
 
 #include "ggnn.h"
 #include "ggnn_launch.h"
+#include "ggnn_regcache.h"
 
 using namespace ggnn;
 
@@ -35,6 +36,7 @@ int fail(int code, const char* fmt, ...) {
   } while (0)
 
 constexpr size_t kMaxLds = 64 * 1024;
+int g_cache_mode = 0;  // 0: registers whenever best and prioq fit 64 entries, 1: always LDS
 
 uint64_t mix64_host(uint64_t x) {
   x ^= x >> 30; x *= 0xBF58476D1CE4E5B9ull;
@@ -133,6 +135,8 @@ GraphDev device_view(const ggnn_graph* g) {
 }
 int row_dtype(const ggnn_graph* g) { return g->norm ? GGNN_F32 : g->dtype; }
 
+bool use_registers(const SearchParams& sp) { return g_cache_mode == 0 && sp.B <= kWave && sp.P <= kWave; }
+
 int make_search_params(int B, int P, int V, int max_iter, float tau, float dnn, SearchParams* sp) {
   if (B < 1 || P < 1 || V < 1 || max_iter < 0) return fail(GGNN_ERR_INVALID, "cache capacities must be positive");
   if (max_iter > V) return fail(GGNN_ERR_INVALID, "max_iter (%d) must not exceed visited_cap (%d)", max_iter, V);
@@ -140,10 +144,28 @@ int make_search_params(int B, int P, int V, int max_iter, float tau, float dnn, 
   sp->H = next_pow2(2 * (max_iter > 0 ? max_iter : 1));
   if (sp->H < 64) sp->H = 64;
   sp->tau = tau; sp->dnn = dnn;
-  if (cache_lds_bytes(sp->B, sp->P, sp->H) > kMaxLds)
+  const size_t need = use_registers(*sp) ? RegCache::lds_bytes(*sp) : LdsCache::lds_bytes(*sp);
+  if (need > kMaxLds)
     return fail(GGNN_ERR_LIMIT, "cache of best=%d prioq=%d visited=%d needs %zu bytes of LDS, limit %zu", B, P, V,
-                cache_lds_bytes(sp->B, sp->P, sp->H), kMaxLds);
+                need, kMaxLds);
   return GGNN_OK;
+}
+
+hipError_t launch_query(const GraphDev& G, int dtype, int metric, const void* queries, int64_t Q, int k,
+                        const SearchParams& sp, int every_layer, int32_t* ids, float* dists, uint32_t* counters,
+                        hipStream_t stream) {
+  return use_registers(sp) ? launch_query_reg(G, dtype, metric, queries, Q, k, sp, every_layer, ids, dists, counters, stream)
+                           : launch_query_lds(G, dtype, metric, queries, Q, k, sp, every_layer, ids, dists, counters, stream);
+}
+hipError_t launch_merge(const GraphDev& G, int dtype, int metric, int l_top, int l_m, const SearchParams& sp,
+                        int32_t* out_rows, float* dnn1, hipStream_t stream) {
+  return use_registers(sp) ? launch_merge_reg(G, dtype, metric, l_top, l_m, sp, out_rows, dnn1, stream)
+                           : launch_merge_lds(G, dtype, metric, l_top, l_m, sp, out_rows, dnn1, stream);
+}
+hipError_t launch_sym_search(const GraphDev& G, int dtype, int metric, int layer, int round, float w_mid,
+                             const SearchParams& sp, const SymBuffers& sb, hipStream_t stream) {
+  return use_registers(sp) ? launch_sym_search_reg(G, dtype, metric, layer, round, w_mid, sp, sb, stream)
+                           : launch_sym_search_lds(G, dtype, metric, layer, round, w_mid, sp, sb, stream);
 }
 
 int ensure_sym_buffers(ggnn_graph* g) {
@@ -200,6 +222,12 @@ struct PhaseTimer {
 extern "C" {
 
 const char* ggnn_last_error(void) { return g_err; }
+
+int ggnn_set_cache_mode(int32_t mode) {
+  if (mode != 0 && mode != 1) return fail(GGNN_ERR_INVALID, "cache mode %d is neither 0 nor 1", mode);
+  g_cache_mode = mode;
+  return GGNN_OK;
+}
 
 void ggnn_free(ggnn_graph* g) {
   if (!g) return;

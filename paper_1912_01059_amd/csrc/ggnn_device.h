@@ -319,11 +319,7 @@ __device__ inline void load_query(QueryRegs<DT, NCH>& q, const uint8_t* row, int
     int chunk = c * kRowLanes + sub;
     uint4 raw = make_uint4(0, 0, 0, 0);
     if (chunk < nchunks) raw = *(const uint4*)(row + (size_t)chunk * 16);
-    chunk_to_float<DT>(raw, &q.v[c * Elem<DT>::per_chunk]);
-    if (DT == 0 && chunk >= nchunks) {
-#pragma unroll
-      for (int e = 0; e < 4; e++) q.v[c * 4 + e] = 0.0f;
-    }
+    chunk_to_float<DT>(raw, &q.v[c * Elem<DT>::per_chunk]);  // chunks past the row read as zeros
   }
 }
 
@@ -418,5 +414,41 @@ __device__ inline void cache_descend(Cache& c, const GraphDev& G, int layer, con
     cache_fetch<DT, NCH, METRIC, PASSES>(c, G, layer, p, q, excl_row);
   }
 }
+
+// The LDS-resident cache behind the interface the kernels use (any capacities that fit in LDS).
+struct LdsCache {
+  static constexpr bool kInRegisters = false;
+  Cache c;
+  __host__ __device__ static size_t lds_bytes(const SearchParams& sp) { return cache_lds_bytes(sp.B, sp.P, sp.H); }
+  __device__ void bind(unsigned char* lds, const SearchParams& sp) { cache_bind(c, lds, sp); }
+  __device__ void init() { cache_init(c); }
+  __device__ void set_radius(float r) { c.radius = r; }
+  template <int DT, int NCH, int METRIC, int PASSES>
+  __device__ void fetch(const GraphDev& G, int layer, int32_t p, const QueryRegs<DT, NCH>& q, int32_t excl_row) {
+    cache_fetch<DT, NCH, METRIC, PASSES>(c, G, layer, p, q, excl_row);
+  }
+  __device__ int32_t pop() { return cache_pop(c); }
+  __device__ void transform(const int32_t* __restrict__ table) { cache_transform(c, table); }
+  __device__ int32_t count() const { return c.nb; }
+  __device__ float first_d() const { return c.d_first; }
+  __device__ uint32_t n_pops() const { return c.pops; }
+  __device__ uint32_t n_evals() const { return c.evals; }
+  __device__ uint32_t n_gathers() const { return c.evals; }
+  __device__ void store_results(int k, int32_t* __restrict__ ids, float* __restrict__ dists) const {
+    for (int j = lane_id(); j < k; j += kWave) {
+      const u64 key = (j < c.nb) ? c.best[j] : make_key(INFINITY, -1);
+      ids[j] = key_id(key);
+      dists[j] = key_d(key);
+    }
+  }
+  __device__ void store_row(int K, int32_t* __restrict__ out) const {
+    const int lane = lane_id();
+    if (lane < K) out[lane] = (lane < c.nb) ? key_id(c.best[lane]) : -1;
+  }
+  __device__ void store_prefs(u64* __restrict__ pref, int32_t* __restrict__ npref) const {
+    for (int i = lane_id(); i < c.nb; i += kWave) pref[i] = c.best[i];
+    if (lane_id() == 0) *npref = c.nb;
+  }
+};
 
 }  // namespace ggnn

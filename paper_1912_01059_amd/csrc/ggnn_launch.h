@@ -22,14 +22,19 @@ struct SymBuffers {
   int32_t* pending;   // 1  number of requests that still have to propose
 };
 
-// search kernels (ggnn_search.hip)
-hipError_t launch_query(const GraphDev& G, int dtype, int metric, const void* queries, int64_t Q, int k,
-                        const SearchParams& sp, int every_layer, int32_t* ids, float* dists, uint32_t* counters,
-                        hipStream_t stream);
-hipError_t launch_merge(const GraphDev& G, int dtype, int metric, int l_top, int l_m, const SearchParams& sp,
-                        int32_t* out_rows, float* dnn1, hipStream_t stream);
-hipError_t launch_sym_search(const GraphDev& G, int dtype, int metric, int layer, int round, float w_mid,
-                             const SearchParams& sp, const SymBuffers& sb, hipStream_t stream);
+// search kernels: best / prioq in registers (ggnn_search_reg.hip, capacities <= 64) or in LDS
+// (ggnn_search_lds.hip); launch_* picks the register variant whenever the capacities allow it
+#define GGNN_SEARCH_LAUNCHERS(SUFFIX)                                                                              \
+  hipError_t launch_query##SUFFIX(const GraphDev& G, int dtype, int metric, const void* queries, int64_t Q, int k, \
+                                  const SearchParams& sp, int every_layer, int32_t* ids, float* dists,             \
+                                  uint32_t* counters, hipStream_t stream);                                         \
+  hipError_t launch_merge##SUFFIX(const GraphDev& G, int dtype, int metric, int l_top, int l_m,                    \
+                                  const SearchParams& sp, int32_t* out_rows, float* dnn1, hipStream_t stream);     \
+  hipError_t launch_sym_search##SUFFIX(const GraphDev& G, int dtype, int metric, int layer, int round, float w_mid,\
+                                       const SearchParams& sp, const SymBuffers& sb, hipStream_t stream);
+GGNN_SEARCH_LAUNCHERS(_reg)
+GGNN_SEARCH_LAUNCHERS(_lds)
+#undef GGNN_SEARCH_LAUNCHERS
 
 // construction kernels (ggnn_build.hip)
 hipError_t launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t stream);

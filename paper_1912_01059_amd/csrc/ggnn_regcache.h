@@ -1,0 +1,300 @@
+// The cache of Sec. 3.1.1 for best and prioq of at most 64 entries each: both lists live in
+// registers, entry i in lane i (packed (distance, id) keys, empty = all ones), so that a sorted
+// insertion is one compare, one whole-wave shift (DPP) and a select, and a pop is a shift the
+// other way.  visited is an exact hash set in LDS; the same table also remembers points that
+// were evaluated and rejected: the threshold of Eq. 2 never grows during a search on one layer,
+// so a point rejected once is rejected whenever it is proposed again, and skipping it changes no
+// result (rejected entries may be left out when the table fills up; visited entries never are).
+#pragma once
+#include "ggnn_device.h"
+
+namespace ggnn {
+
+constexpr u64 kEmptyKey = ~0ull;
+
+// whole-wave shift by one lane (GFX9 DPP wave_shr:1 / wave_shl:1); the vacated lane gets `fill`
+__device__ __forceinline__ u64 wave_shift_up(u64 v, u64 fill) {
+  int lo = __builtin_amdgcn_update_dpp((int)(uint32_t)fill, (int)(uint32_t)v, 0x138, 0xf, 0xf, false);
+  int hi = __builtin_amdgcn_update_dpp((int)(uint32_t)(fill >> 32), (int)(uint32_t)(v >> 32), 0x138, 0xf, 0xf, false);
+  return ((u64)(uint32_t)hi << 32) | (uint32_t)lo;
+}
+__device__ __forceinline__ u64 wave_shift_down(u64 v, u64 fill) {
+  int lo = __builtin_amdgcn_update_dpp((int)(uint32_t)fill, (int)(uint32_t)v, 0x130, 0xf, 0xf, false);
+  int hi = __builtin_amdgcn_update_dpp((int)(uint32_t)(fill >> 32), (int)(uint32_t)(v >> 32), 0x130, 0xf, 0xf, false);
+  return ((u64)(uint32_t)hi << 32) | (uint32_t)lo;
+}
+__device__ __forceinline__ u64 read_lane_u64(u64 v, int lane) {
+  uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, lane);
+  uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), lane);
+  return ((u64)hi << 32) | lo;
+}
+
+struct RegCache {
+  static constexpr bool kInRegisters = true;
+  u64 best, pq;                 // lane i: entry i, kEmptyKey beyond the fill level / capacity
+  int32_t B, P, nb, np;
+  int32_t iter, max_iter;
+  float tau, dnn, radius;
+  int32_t* hash; int32_t hmask;  // LDS: visited ids, and rejected ids with the top bit set
+  int32_t nrej, rej_cap;
+  u64* stage;                    // LDS: 4 x 64 keys for Transform
+  int32_t* surv_id; int32_t* surv_row; float* surv_d;  // LDS, 64 each
+  uint32_t pops, evals, gathers;
+
+  // hash slots: 4 per possible visited id (half of the table is the most ever occupied)
+  __host__ __device__ static int hash_slots(int max_iter) {
+    int h = 64;
+    while (h < 4 * max_iter) h <<= 1;
+    return h;
+  }
+  __host__ __device__ static size_t lds_bytes(const SearchParams& sp) {
+    return (size_t)hash_slots(sp.max_iter) * 4 + 4 * 64 * 8 + 3 * 64 * 4;
+  }
+
+  __device__ void bind(unsigned char* lds, const SearchParams& sp) {
+    B = sp.B; P = sp.P; max_iter = sp.max_iter; tau = sp.tau; dnn = sp.dnn;
+    const int H = hash_slots(sp.max_iter);
+    stage = (u64*)lds;
+    hash = (int32_t*)(stage + 4 * 64);
+    hmask = H - 1;
+    surv_id = hash + H;
+    surv_row = surv_id + 64;
+    surv_d = (float*)(surv_row + 64);
+    rej_cap = H / 2 - sp.max_iter;
+  }
+  __device__ void clear_hash() {
+    for (int i = lane_id(); i <= hmask; i += kWave) hash[i] = -1;
+    nrej = 0;
+    wave_sync();
+  }
+  // Alg. 2 Init
+  __device__ void init() {
+    best = pq = kEmptyKey;
+    nb = np = 0; iter = 0; pops = evals = gathers = 0;
+    radius = INFINITY;
+    clear_hash();
+  }
+  __device__ void set_radius(float r) { radius = r; }
+
+  // 0: unknown, 1: visited, 2: evaluated before and rejected
+  __device__ int probe(int32_t id) const {
+    uint32_t h = mix32((uint32_t)id) & (uint32_t)hmask;
+    int32_t v;
+    while ((v = hash[h]) != -1) {
+      if ((v & 0x7FFFFFFF) == id) return (v < 0) ? 2 : 1;
+      h = (h + 1) & (uint32_t)hmask;
+    }
+    return 0;
+  }
+  __device__ void insert_visited(int32_t id) {  // uniform call
+    if (lane_id() == 0) {
+      uint32_t h = mix32((uint32_t)id) & (uint32_t)hmask;
+      while (hash[h] != -1) h = (h + 1) & (uint32_t)hmask;
+      hash[h] = id;
+    }
+    wave_sync();
+  }
+  __device__ void insert_rejected(bool mine, int32_t id) {
+    const int cnt = __popcll(__ballot(mine));
+    if (cnt == 0 || nrej + cnt > rej_cap) return;
+    nrej += cnt;
+    if (mine) {
+      uint32_t h = mix32((uint32_t)id) & (uint32_t)hmask;
+      while (atomicCAS(&hash[h], -1, (int32_t)((uint32_t)id | 0x80000000u)) != -1) h = (h + 1) & (uint32_t)hmask;
+    }
+    wave_sync();
+  }
+
+  __device__ float first_d() const { return key_d(read_lane_u64(best, 0)); }
+  __device__ int32_t count() const { return nb; }
+  __device__ uint32_t n_pops() const { return pops; }
+  __device__ uint32_t n_evals() const { return evals; }
+  __device__ uint32_t n_gathers() const { return gathers; }
+  // Eq. 2
+  __device__ float thr() const {
+    if (nb == 0) return INFINITY;
+    const float d1 = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(best >> 32), 0));
+    const float dk = (nb < B) ? INFINITY
+                              : __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(best >> 32), B - 1));
+    const float xi = tau * fminf(d1, dnn);
+    return dk + xi;
+  }
+
+  // sorted insertion into a register list; entries beyond `cap` fall off
+  __device__ static void list_insert(u64& L, int32_t& n, int32_t cap, u64 key) {
+    const int lane = lane_id();
+    const bool lt = L < key;
+    const int pos = __popcll(__ballot(lt));
+    const u64 up = wave_shift_up(L, key);
+    L = lt ? L : (lane == pos ? key : up);
+    if (lane >= cap) L = kEmptyKey;
+    if (pos < cap && n < cap) n++;
+  }
+  // Alg. 2 Push
+  __device__ void push(u64 key) {
+    list_insert(best, nb, B, key);
+    list_insert(pq, np, P, key);
+  }
+
+  // Alg. 2 Pop
+  __device__ int32_t pop() {
+    if (np == 0 || iter >= max_iter) return -1;
+    const u64 head = read_lane_u64(pq, 0);
+    const float d = key_d(head);
+    if (!(d <= thr() && d <= radius)) return -1;
+    pq = wave_shift_down(pq, kEmptyKey);
+    np--;
+    const int32_t id = key_id(head);
+    insert_visited(id);
+    iter++;
+    pops++;
+    return id;
+  }
+
+  // Alg. 4 Transform (see the LDS variant in ggnn_device.h for the reading); staged through LDS
+  __device__ void transform(const int32_t* __restrict__ table) {
+    const int lane = lane_id();
+    u64* sb = stage; u64* sp = stage + 64; u64* out = stage + 128;
+    if (lane < nb) best = (best & 0xFFFFFFFF00000000ull) | (uint32_t)table[key_id(best)];
+    if (lane < np) pq = (pq & 0xFFFFFFFF00000000ull) | (uint32_t)table[key_id(pq)];
+    sb[lane] = best;
+    wave_sync();
+    // best: same distances, ties re-ordered by the new ids
+    if (lane < nb) {
+      int r = 0;
+      for (int j = 0; j < nb; j++) r += sb[j] < best;
+      out[r] = best;
+    }
+    wave_sync();
+    best = (lane < nb) ? out[lane] : kEmptyKey;
+    wave_sync();
+    sb[lane] = best;
+    // prioq entries that are also in best are dropped from the union
+    bool dup = false;
+    if (lane < np)
+      for (int j = 0; j < nb; j++) dup = dup || key_id(out[j]) == key_id(pq);
+    sp[lane] = (lane < np && !dup) ? pq : kEmptyKey;
+    wave_sync();
+    const int m = nb + __popcll(__ballot(lane < np && !dup));
+    // rank of every entry in the union; the P smallest form the new prioq
+    int rb = lane, rp = 0;
+    for (int j = 0; j < np; j++) rb += sp[j] < best;
+    const u64 mine = sp[lane];
+    for (int j = 0; j < nb; j++) rp += sb[j] < mine;
+    for (int j = 0; j < np; j++) rp += sp[j] < mine;
+    wave_sync();
+    if (lane < nb && rb < kWave) out[rb] = best;
+    if (mine != kEmptyKey && rp < kWave) out[rp] = mine;
+    wave_sync();
+    np = m < P ? m : P;
+    pq = (lane < np) ? out[lane] : kEmptyKey;
+    iter = 0;
+    clear_hash();
+  }
+
+  // Alg. 2 Fetch
+  template <int DT, int NCH, int METRIC, int PASSES>
+  __device__ void fetch(const GraphDev& G, int layer, int32_t p, const QueryRegs<DT, NCH>& q, int32_t excl_row) {
+    const int lane = lane_id();
+    bool alive = p >= 0;
+    int32_t row = -1;
+    if (alive) {
+      row = (layer == 0) ? p : G.to_base[layer][p];
+      alive = row != excl_row;
+    }
+    bool seen_rejected = false;
+    if (alive) {
+      const int kind = probe(p);
+      alive = kind == 0;
+      seen_rejected = kind == 2;
+    }
+    // membership in best / prioq: one broadcast per remaining proposal
+    u64 cand = __ballot(alive);
+    u64 known = 0;
+    while (cand) {
+      const int j = __builtin_ctzll(cand);
+      cand &= cand - 1;
+      const int32_t pid = __builtin_amdgcn_readlane(p, j);
+      const bool hit = key_id(best) == pid || key_id(pq) == pid;
+      if (__ballot(hit)) known |= 1ull << j;
+    }
+    alive = alive && !((known >> lane) & 1);
+    const u64 mask = __ballot(alive);
+    const int ns = __popcll(mask);
+    // a point rejected before would be evaluated and rejected again: counted, not gathered
+    evals += ns + __popcll(__ballot(seen_rejected));
+    if (ns == 0) return;
+    gathers += ns;
+    if (alive) {
+      const int r = __popcll(mask & ((1ull << lane) - 1));
+      surv_id[r] = p;
+      surv_row[r] = row;
+    }
+    wave_sync();
+    const int sub = lane & (kRowLanes - 1), grp = lane / kRowLanes;
+    for (int b0 = 0; b0 < ns; b0 += kRowsPerPass * PASSES) {
+      uint4 raw[PASSES][NCH];
+#pragma unroll
+      for (int ps = 0; ps < PASSES; ps++) {
+        const int r = b0 + ps * kRowsPerPass + grp;
+        const bool act = r < ns;
+        const uint8_t* ptr = G.rows + (size_t)(act ? surv_row[r] : 0) * (size_t)G.row_bytes;
+#pragma unroll
+        for (int ch = 0; ch < NCH; ch++) {
+          const int chunk = ch * kRowLanes + sub;
+          raw[ps][ch] = make_uint4(0, 0, 0, 0);
+          if (act && chunk < G.nchunks) raw[ps][ch] = *(const uint4*)(ptr + (size_t)chunk * 16);
+        }
+      }
+#pragma unroll
+      for (int ps = 0; ps < PASSES; ps++) {
+        if (b0 + ps * kRowsPerPass < ns) {  // uniform: skip passes without rows
+          const int r = b0 + ps * kRowsPerPass + grp;
+          const float d = row_distance<DT, NCH, METRIC>(q, raw[ps]);
+          if (r < ns && sub == 0) surv_d[r] = d;
+        }
+      }
+    }
+    wave_sync();
+    // Survivors are pushed in list order with the threshold re-evaluated after every push.  The
+    // threshold only shrinks, so whoever fails the threshold as it stands now fails later too:
+    // only the others go through the sequential loop.
+    const bool mine = lane < ns;
+    const float d = mine ? surv_d[lane] : INFINITY;
+    const int32_t id = mine ? surv_id[lane] : -1;
+    u64 todo = __ballot(mine && d <= thr() && d <= radius);
+    u64 accepted = 0;
+    while (todo) {
+      const int r = __builtin_ctzll(todo);
+      todo &= todo - 1;
+      const float dr = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(d), r));
+      if (dr <= thr()) {
+        push(make_key(dr, __builtin_amdgcn_readlane(id, r)));
+        accepted |= 1ull << r;
+      }
+    }
+    insert_rejected(mine && !((accepted >> lane) & 1), id);
+  }
+
+  // results
+  __device__ void store_results(int k, int32_t* __restrict__ ids, float* __restrict__ dists) const {
+    const int lane = lane_id();
+    for (int j = lane; j < k; j += kWave) {
+      const u64 key = (j < kWave) ? best : kEmptyKey;  // k > 64 cannot hold more than 64 results
+      const bool ok = j < nb;
+      ids[j] = ok ? key_id(key) : -1;
+      dists[j] = ok ? key_d(key) : INFINITY;
+    }
+  }
+  __device__ void store_row(int K, int32_t* __restrict__ out) const {
+    const int lane = lane_id();
+    if (lane < K) out[lane] = (lane < nb) ? key_id(best) : -1;
+  }
+  __device__ void store_prefs(u64* __restrict__ pref, int32_t* __restrict__ npref) const {
+    const int lane = lane_id();
+    if (lane < nb) pref[lane] = best;
+    if (lane == 0) *npref = nb;
+  }
+};
+
+}  // namespace ggnn

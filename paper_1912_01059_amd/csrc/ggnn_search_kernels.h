@@ -1,71 +1,85 @@
 // Search kernels: user query (Alg. 1 / Alg. 4, Sec. 4.4), construction query (Alg. 3 Merge,
 // Alg. 4) and the symmetric-linking query (Alg. 5, Sec. 4.2.1).  One wavefront per query.
+// The kernels are templates over the cache implementation (registers or LDS), the element type,
+// the number of 16-byte chunks a lane holds of a row, and the metric.
+#pragma once
 #include "ggnn_launch.h"
+#include "ggnn_regcache.h"
 
 namespace ggnn {
 
-constexpr int kPasses = 3;  // 8 rows per pass: 24 rows in flight per wavefront
+constexpr int kPasses = 3;  // 8 rows per pass: up to 24 rows in flight per wavefront
 
-template <int DT, int NCH, int METRIC>
+template <int DT, int NCH>
 __device__ inline void normalise_query(QueryRegs<DT, NCH>& q) {
   constexpr int E = Elem<DT>::per_chunk;
   float acc = 0.0f;
 #pragma unroll
   for (int i = 0; i < NCH * E; i++) acc = __builtin_fmaf(q.v[i], q.v[i], acc);
   acc = row_reduce(acc);
-  float nrm = __builtin_sqrtf(acc);
+  const float nrm = __builtin_sqrtf(acc);
   if (nrm > 0.0f) {
 #pragma unroll
     for (int i = 0; i < NCH * E; i++) q.v[i] = q.v[i] / nrm;
   }
 }
 
-template <int DT, int NCH, int METRIC>
+// Alg. 1 main loop on one layer
+template <class C, int DT, int NCH, int METRIC>
+__device__ inline void descend(C& c, const GraphDev& G, int layer, const QueryRegs<DT, NCH>& q, int32_t excl_row) {
+  const int lane = lane_id();
+  const int32_t* __restrict__ E = G.edges[layer];
+  int32_t a;
+  while ((a = c.pop()) >= 0) {
+    const int32_t p = (lane < G.K) ? E[(size_t)a * G.K + lane] : -1;
+    c.template fetch<DT, NCH, METRIC, kPasses>(G, layer, p, q, excl_row);
+  }
+}
+
+template <class C, int DT, int NCH, int METRIC>
 __global__ __launch_bounds__(kWave) void query_kernel(GraphDev G, const uint8_t* __restrict__ queries, int k,
                                                       SearchParams sp, int every_layer, int32_t* __restrict__ ids,
                                                       float* __restrict__ dists, uint32_t* __restrict__ counters) {
   extern __shared__ __align__(16) unsigned char lds[];
   const int lane = lane_id();
   const int64_t qi = blockIdx.x;
-  Cache c;
-  cache_bind(c, lds, sp);
-  cache_init(c);
+  C c;
+  c.bind(lds, sp);
+  c.init();
   QueryRegs<DT, NCH> q;
   load_query<DT, NCH>(q, queries + (size_t)qi * (size_t)G.row_bytes, G.nchunks);
-  if (METRIC == 1) normalise_query<DT, NCH, METRIC>(q);
+  if (METRIC == 1) normalise_query<DT, NCH>(q);
 
   // start points: the s points of the top layer (Sec. 3.1, Sec. 4.4)
   const int top = G.L - 1;
-  cache_fetch<DT, NCH, METRIC, kPasses>(c, G, top, lane < G.s ? lane : -1, q, -1);
+  c.template fetch<DT, NCH, METRIC, kPasses>(G, top, lane < G.s ? lane : -1, q, -1);
   if (every_layer) {
     for (int l = top - 1; l >= 0; l--) {
-      cache_transform(c, G.to_lower[l + 1]);
-      cache_descend<DT, NCH, METRIC, kPasses>(c, G, l, q, -1);
+      c.transform(G.to_lower[l + 1]);
+      descend<C, DT, NCH, METRIC>(c, G, l, q, -1);
     }
   } else {
-    cache_transform(c, G.to_base[top]);
-    cache_descend<DT, NCH, METRIC, kPasses>(c, G, 0, q, -1);
+    c.transform(G.to_base[top]);
+    descend<C, DT, NCH, METRIC>(c, G, 0, q, -1);
   }
-  for (int j = lane; j < k; j += kWave) {
-    u64 key = (j < c.nb) ? c.best[j] : make_key(INFINITY, -1);
-    ids[(size_t)qi * k + j] = key_id(key);
-    dists[(size_t)qi * k + j] = key_d(key);
-  }
+  c.store_results(k, ids + (size_t)qi * k, dists + (size_t)qi * k);
   if (counters && lane == 0) {
-    counters[2 * qi] = c.pops;
-    counters[2 * qi + 1] = c.evals;
+    counters[4 * qi + 0] = c.n_pops();
+    counters[4 * qi + 1] = c.n_evals();
+    counters[4 * qi + 2] = c.n_gathers();
+    counters[4 * qi + 3] = 0;
   }
 }
 
-template <int DT, int NCH, int METRIC>
+template <class C, int DT, int NCH, int METRIC>
 __global__ __launch_bounds__(kWave) void merge_kernel(GraphDev G, int l_top, int l_m, SearchParams sp,
                                                       int32_t* __restrict__ out_rows, float* __restrict__ dnn1) {
   extern __shared__ __align__(16) unsigned char lds[];
   const int lane = lane_id();
   const int64_t z = blockIdx.x;
-  Cache c;
-  cache_bind(c, lds, sp);
-  cache_init(c);
+  C c;
+  c.bind(lds, sp);
+  c.init();
   const int32_t zrow = (l_m == 0) ? (int32_t)z : G.to_base[l_m][z];
   QueryRegs<DT, NCH> q;
   load_query<DT, NCH>(q, G.rows + (size_t)zrow * (size_t)G.row_bytes, G.nchunks);
@@ -76,28 +90,28 @@ __global__ __launch_bounds__(kWave) void merge_kernel(GraphDev G, int l_top, int
     // cache keeps exactly the K smallest (a rejected point lies beyond the current K-th).
     int32_t p = -1;
     if (l_m == 0) {
-      int64_t lo = seg0_lo(G, seg), hi = seg0_lo(G, seg + 1);
+      const int64_t lo = seg0_lo(G, seg), hi = seg0_lo(G, seg + 1);
       if (lo + lane < hi) p = (int32_t)perm_fwd(G, lo + lane);
     } else if (lane < G.s) {
       p = (int32_t)(seg * G.s + lane);
     }
-    cache_fetch<DT, NCH, METRIC, kPasses>(c, G, l_m, p, q, zrow);
+    c.template fetch<DT, NCH, METRIC, kPasses>(G, l_m, p, q, zrow);
   } else {
     for (int l = l_m; l < l_top; l++) seg /= G.g;  // top segment of z's sub-graph
-    cache_fetch<DT, NCH, METRIC, kPasses>(c, G, l_top, lane < G.s ? (int32_t)(seg * G.s + lane) : -1, q, zrow);
+    c.template fetch<DT, NCH, METRIC, kPasses>(G, l_top, lane < G.s ? (int32_t)(seg * G.s + lane) : -1, q, zrow);
     for (int l = l_top - 1; l >= l_m; l--) {
-      cache_transform(c, G.to_lower[l + 1]);
-      cache_descend<DT, NCH, METRIC, kPasses>(c, G, l, q, zrow);
+      c.transform(G.to_lower[l + 1]);
+      descend<C, DT, NCH, METRIC>(c, G, l, q, zrow);
     }
   }
-  if (lane < G.K) out_rows[(size_t)z * G.K + lane] = (lane < c.nb) ? key_id(c.best[lane]) : -1;
-  if (l_m == 0 && lane == 0) dnn1[z] = (c.nb > 0) ? c.d_first : 0.0f;
+  c.store_row(G.K, out_rows + (size_t)z * G.K);
+  if (l_m == 0 && lane == 0) dnn1[z] = (c.count() > 0) ? c.first_d() : 0.0f;
 }
 
 // Alg. 5 for neighbour number `round` of every point z: is there a path from x back to z
 // inside the sphere around q_m = z + w (x - z) that touches x (Sec. 4.2.1)?  If not, the
 // best list of the search is kept as z's candidates for an inverse link.
-template <int DT, int NCH, int METRIC>
+template <class C, int DT, int NCH, int METRIC>
 __global__ __launch_bounds__(kWave) void sym_search_kernel(GraphDev G, int layer, int round, float w_mid,
                                                            SearchParams sp, SymBuffers sb) {
   extern __shared__ __align__(16) unsigned char lds[];
@@ -112,13 +126,13 @@ __global__ __launch_bounds__(kWave) void sym_search_kernel(GraphDev G, int layer
   {
     // a direct link back from x makes the search unnecessary
     const int nix = sb.ninv[x];
-    bool hit = (lane < knn && Ed[(size_t)x * G.K + lane] == (int32_t)z) ||
-               (lane < nix && sb.inv[(size_t)x * ksym + lane] == (int32_t)z);
+    const bool hit = (lane < knn && Ed[(size_t)x * G.K + lane] == (int32_t)z) ||
+                     (lane < nix && sb.inv[(size_t)x * ksym + lane] == (int32_t)z);
     if (__ballot(hit)) return;
   }
-  Cache c;
-  cache_bind(c, lds, sp);
-  cache_init(c);
+  C c;
+  c.bind(lds, sp);
+  c.init();
   const int32_t zrow = (layer == 0) ? (int32_t)z : G.to_base[layer][z];
   const int32_t xrow = (layer == 0) ? x : G.to_base[layer][x];
   QueryRegs<DT, NCH> q, xq;
@@ -126,8 +140,8 @@ __global__ __launch_bounds__(kWave) void sym_search_kernel(GraphDev G, int layer
   load_query<DT, NCH>(xq, G.rows + (size_t)xrow * (size_t)G.row_bytes, G.nchunks);
 #pragma unroll
   for (int i = 0; i < NCH * E; i++) {
-    float t = xq.v[i] - q.v[i];
-    float u = w_mid * t;
+    const float t = xq.v[i] - q.v[i];
+    const float u = w_mid * t;
     q.v[i] = q.v[i] + u;
   }
   {
@@ -136,75 +150,73 @@ __global__ __launch_bounds__(kWave) void sym_search_kernel(GraphDev G, int layer
     const int sub = lane & (kRowLanes - 1);
 #pragma unroll
     for (int ch = 0; ch < NCH; ch++) {
-      int chunk = ch * kRowLanes + sub;
+      const int chunk = ch * kRowLanes + sub;
       raw[ch] = make_uint4(0, 0, 0, 0);
       if (chunk < G.nchunks) raw[ch] = *(const uint4*)(G.rows + (size_t)xrow * (size_t)G.row_bytes + (size_t)chunk * 16);
     }
-    c.radius = row_distance<DT, NCH, METRIC>(q, raw);
+    c.set_radius(row_distance<DT, NCH, METRIC>(q, raw));
   }
-  cache_fetch<DT, NCH, METRIC, kPasses>(c, G, layer, lane == 0 ? x : -1, q, -1);
+  c.template fetch<DT, NCH, METRIC, kPasses>(G, layer, lane == 0 ? x : -1, q, -1);
   bool found = false;
   int32_t a;
-  while ((a = cache_pop(c)) >= 0) {
+  while ((a = c.pop()) >= 0) {
     const int nia = sb.ninv[a];
     int32_t p = -1;
     if (lane < knn) p = Ed[(size_t)a * G.K + lane];
     else if (lane < knn + nia) p = sb.inv[(size_t)a * ksym + (lane - knn)];
     if (__ballot(p == (int32_t)z)) { found = true; break; }
-    cache_fetch<DT, NCH, METRIC, kPasses>(c, G, layer, p, q, -1);
+    c.template fetch<DT, NCH, METRIC, kPasses>(G, layer, p, q, -1);
   }
-  if (!found && c.nb > 0) {
-    for (int i = lane; i < c.nb; i += kWave) sb.pref[(size_t)z * sp.B + i] = c.best[i];
-    if (lane == 0) sb.npref[z] = c.nb;
-  }
+  if (!found && c.count() > 0) c.store_prefs(sb.pref + (size_t)z * sp.B, sb.npref + z);
 }
 
 // ---- dispatch over element type, chunks per lane and metric ---------------------------
-#define GGNN_DISPATCH(KERNEL, ...)                                                                      \
+#define GGNN_DISPATCH(C, KERNEL, ...)                                                                   \
   do {                                                                                                  \
     const int need = (G.nchunks + kRowLanes - 1) / kRowLanes;                                           \
     if (metric == 1) {                                                                                  \
-      if (need <= 1) KERNEL<0, 1, 1><<<grid, kWave, lds, stream>>>(__VA_ARGS__);                        \
-      else if (need <= 3) KERNEL<0, 3, 1><<<grid, kWave, lds, stream>>>(__VA_ARGS__);                   \
-      else if (need <= 4) KERNEL<0, 4, 1><<<grid, kWave, lds, stream>>>(__VA_ARGS__);                   \
-      else if (need <= 8) KERNEL<0, 8, 1><<<grid, kWave, lds, stream>>>(__VA_ARGS__);                   \
+      if (need <= 1) KERNEL<C, 0, 1, 1><<<grid, kWave, lds, stream>>>(__VA_ARGS__);                     \
+      else if (need <= 3) KERNEL<C, 0, 3, 1><<<grid, kWave, lds, stream>>>(__VA_ARGS__);                \
+      else if (need <= 4) KERNEL<C, 0, 4, 1><<<grid, kWave, lds, stream>>>(__VA_ARGS__);                \
+      else if (need <= 8) KERNEL<C, 0, 8, 1><<<grid, kWave, lds, stream>>>(__VA_ARGS__);                \
       else return hipErrorInvalidValue;                                                                 \
     } else if (dtype == 0) {                                                                            \
-      if (need <= 1) KERNEL<0, 1, 0><<<grid, kWave, lds, stream>>>(__VA_ARGS__);                        \
-      else if (need <= 3) KERNEL<0, 3, 0><<<grid, kWave, lds, stream>>>(__VA_ARGS__);                   \
-      else if (need <= 4) KERNEL<0, 4, 0><<<grid, kWave, lds, stream>>>(__VA_ARGS__);                   \
-      else if (need <= 8) KERNEL<0, 8, 0><<<grid, kWave, lds, stream>>>(__VA_ARGS__);                   \
+      if (need <= 1) KERNEL<C, 0, 1, 0><<<grid, kWave, lds, stream>>>(__VA_ARGS__);                     \
+      else if (need <= 3) KERNEL<C, 0, 3, 0><<<grid, kWave, lds, stream>>>(__VA_ARGS__);                \
+      else if (need <= 4) KERNEL<C, 0, 4, 0><<<grid, kWave, lds, stream>>>(__VA_ARGS__);                \
+      else if (need <= 8) KERNEL<C, 0, 8, 0><<<grid, kWave, lds, stream>>>(__VA_ARGS__);                \
       else return hipErrorInvalidValue;                                                                 \
     } else {                                                                                            \
-      if (need <= 1) KERNEL<1, 1, 0><<<grid, kWave, lds, stream>>>(__VA_ARGS__);                        \
-      else if (need <= 2) KERNEL<1, 2, 0><<<grid, kWave, lds, stream>>>(__VA_ARGS__);                   \
+      if (need <= 1) KERNEL<C, 1, 1, 0><<<grid, kWave, lds, stream>>>(__VA_ARGS__);                     \
+      else if (need <= 2) KERNEL<C, 1, 2, 0><<<grid, kWave, lds, stream>>>(__VA_ARGS__);                \
       else return hipErrorInvalidValue;                                                                 \
     }                                                                                                   \
   } while (0)
 
-hipError_t launch_query(const GraphDev& G, int dtype, int metric, const void* queries, int64_t Q, int k,
-                        const SearchParams& sp, int every_layer, int32_t* ids, float* dists, uint32_t* counters,
-                        hipStream_t stream) {
+template <class C>
+hipError_t launch_query_t(const GraphDev& G, int dtype, int metric, const void* queries, int64_t Q, int k,
+                          const SearchParams& sp, int every_layer, int32_t* ids, float* dists, uint32_t* counters,
+                          hipStream_t stream) {
   if (Q <= 0) return hipSuccess;
   const dim3 grid((unsigned)Q);
-  const size_t lds = cache_lds_bytes(sp.B, sp.P, sp.H);
-  GGNN_DISPATCH(query_kernel, G, (const uint8_t*)queries, k, sp, every_layer, ids, dists, counters);
+  const size_t lds = C::lds_bytes(sp);
+  GGNN_DISPATCH(C, query_kernel, G, (const uint8_t*)queries, k, sp, every_layer, ids, dists, counters);
   return hipGetLastError();
 }
-
-hipError_t launch_merge(const GraphDev& G, int dtype, int metric, int l_top, int l_m, const SearchParams& sp,
-                        int32_t* out_rows, float* dnn1, hipStream_t stream) {
+template <class C>
+hipError_t launch_merge_t(const GraphDev& G, int dtype, int metric, int l_top, int l_m, const SearchParams& sp,
+                          int32_t* out_rows, float* dnn1, hipStream_t stream) {
   const dim3 grid((unsigned)G.n[l_m]);
-  const size_t lds = cache_lds_bytes(sp.B, sp.P, sp.H);
-  GGNN_DISPATCH(merge_kernel, G, l_top, l_m, sp, out_rows, dnn1);
+  const size_t lds = C::lds_bytes(sp);
+  GGNN_DISPATCH(C, merge_kernel, G, l_top, l_m, sp, out_rows, dnn1);
   return hipGetLastError();
 }
-
-hipError_t launch_sym_search(const GraphDev& G, int dtype, int metric, int layer, int round, float w_mid,
-                             const SearchParams& sp, const SymBuffers& sb, hipStream_t stream) {
+template <class C>
+hipError_t launch_sym_search_t(const GraphDev& G, int dtype, int metric, int layer, int round, float w_mid,
+                               const SearchParams& sp, const SymBuffers& sb, hipStream_t stream) {
   const dim3 grid((unsigned)G.n[layer]);
-  const size_t lds = cache_lds_bytes(sp.B, sp.P, sp.H);
-  GGNN_DISPATCH(sym_search_kernel, G, layer, round, w_mid, sp, sb);
+  const size_t lds = C::lds_bytes(sp);
+  GGNN_DISPATCH(C, sym_search_kernel, G, layer, round, w_mid, sp, sb);
   return hipGetLastError();
 }
 
