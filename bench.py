@@ -51,11 +51,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="sift1m")
     ap.add_argument("--n", type=int, default=None, help="override the number of base points (debugging)")
-    ap.add_argument("--levels", type=int, default=4)
+    ap.add_argument("--levels", type=int, default=3)
     ap.add_argument("--slack", type=float, default=0.05, help="tau_q of the timed operating point")
     ap.add_argument("--beam", type=int, default=10)
-    ap.add_argument("--visited-cap", type=int, default=512)
+    ap.add_argument("--visited-cap", type=int, default=64, help="visited capacity = iteration limit per layer")
     ap.add_argument("--pq-cap", type=int, default=64)
+    ap.add_argument("--large-batch", type=int, default=100_000, help="also time a batch of this many queries (0 = skip)")
     ap.add_argument("--sweep", action="store_true", help="also trace the QPS-vs-recall curve")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=2000)
@@ -101,8 +102,8 @@ def main():
     curve = []
     if args.sweep:
         sweep = [dict(beam=10, slack=sl, visited_cap=v, pq_cap=64)
-                 for (sl, v) in [(0.02, 512), (0.035, 512), (0.05, 512), (0.065, 512), (0.08, 512), (0.1, 1024),
-                                 (0.15, 1024), (0.2, 1024), (0.3, 1024)]]
+                 for (sl, v) in [(0.02, 64), (0.03, 64), (0.04, 64), (0.05, 64), (0.065, 96), (0.08, 128), (0.1, 192),
+                                 (0.15, 384), (0.2, 512), (0.3, 1024)]]
         for op in sweep:
             okw = dict(pq_cap=op["pq_cap"], visited_cap=op["visited_cap"], every_layer=True)
             _, _, c = graph.query(queries, k, op["beam"], op["slack"], counters=True, out=(ids, dists), **okw)
@@ -137,6 +138,40 @@ def main():
     ms_per_step = wall_ms / args.steps
     qps = Q / ms_per_step * 1e3
     final_recall = recall_at_k(dists, gt_d)
+
+    # ---- steady state: a batch large enough to keep every CU busy (the paper's own batch-size
+    # study peaks near 95 000 queries), and the rate at which this GPU serves random row gathers
+    large = None
+    if args.large_batch > 0 and cfg["kind"] == "gmm":
+        qn = ggnn_inputs.gmm_int(args.large_batch, D, cfg["components"], cfg["sigma"], cfg["data_seed"],
+                                 cfg["query_seed"] + 7, cfg["dtype"])
+        ql = torch.from_numpy(qn).to(dev)
+        lids, ld, lcnt = graph.query(ql, k, chosen["beam"], chosen["slack"], counters=True, **kw)
+        e0l, e1l = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0l.record(stream)
+        for _ in range(3):
+            graph.query(ql, k, chosen["beam"], chosen["slack"], out=(lids, ld), asynchronous=True, **kw)
+        e1l.record(stream)
+        torch.cuda.synchronize()
+        lms = e0l.elapsed_time(e1l) / 3
+        lc = lcnt.double().sum(0).tolist()
+        lbytes = len(qn) * (D * esize + k * 8) + lc[0] * K * 4 + lc[2] * (4 + D * esize)
+        large = {"queries": len(qn), "qps": round(len(qn) / lms * 1e3, 1), "kernel_ms": round(lms, 3),
+                 "achieved_GBps": round(lbytes / (lms * 1e-3) / 1e9, 1),
+                 "frac_of_hbm_peak": round(lbytes / (lms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        del ql, lids, ld, lcnt
+    n_probe = 12_000_000
+    pids = torch.randint(0, N, (n_probe,), device=dev, dtype=torch.int32)
+    pout = ggnn.gather_probe(base, pids, 1200)
+    torch.cuda.synchronize()
+    e0g, e1g = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0g.record(stream)
+    for _ in range(3):
+        ggnn.gather_probe(base, pids, 1200, out=pout)
+    e1g.record(stream)
+    torch.cuda.synchronize()
+    gather_ceiling = round(n_probe * (D * esize + 4) / (e0g.elapsed_time(e1g) / 3 * 1e-3) / 1e9, 1)
+    del pids, pout
 
     # ---- roofline of the search kernel: algorithmic bytes per launch / kernel time ----
     # per query: the query vector, one adjacency row per pop, one base row (and its id) per row
@@ -186,6 +221,8 @@ def main():
         "graph_bytes": graph.graph_bytes,
         "pops_per_query": round(cnt[0] / Q, 1), "dist_evals_per_query": round(cnt[1] / Q, 1),
         "rows_gathered_per_query": round(cnt[2] / Q, 1),
+        "large_batch": large,
+        "random_row_gather_ceiling_GBps": gather_ceiling,
         "curve": curve,
         "roofline": roofline,
         "cpu_baseline": cpu,

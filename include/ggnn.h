@@ -128,9 +128,9 @@ int ggnn_query(const ggnn_graph* g, const void* queries_dev, int64_t Q, int32_t 
  * max_iter: iteration limit per layer, must be <= visited_cap so that visited never
  * forgets a point.  every_layer: 0 = Sec. 4.4 shortcut, 1 = search every layer on the way
  * down (Alg. 4).  stream: hipStream_t (NULL = the graph's stream).  counters_dev:
- * optional Q x 4 uint32 (device), per query: pops; distance evaluations of the method (Alg. 2
- * Fetch: a point counts again each time it is proposed while unknown to the cache); base rows
- * actually gathered (fewer when re-evaluations of rejected points are skipped); 0.
+ * optional Q x 4 uint32 (device), per query: pops (iterations of Alg. 1); distance evaluations of
+ * the method (Alg. 2 Fetch: a point counts again each time it is proposed while unknown to the
+ * cache); base rows actually gathered (fewer: re-evaluations of rejected points are skipped); 0.
  * asynchronous != 0 returns right after the launch (no synchronisation). */
 int ggnn_query_ex(const ggnn_graph* g, const void* queries_dev, int64_t Q, int32_t k, int32_t beam, float slack,
                   int32_t pq_cap, int32_t visited_cap, int32_t max_iter, int32_t every_layer, void* stream,
@@ -159,6 +159,14 @@ int ggnn_graph_export_inv_count(const ggnn_graph* g, int32_t layer, int32_t* cou
 /* Where best and prioq live during a search: 0 (default) in registers whenever both hold at most
  * 64 entries, otherwise in LDS; 1 always in LDS.  Results do not depend on it.  Process-wide. */
 int ggnn_set_cache_mode(int32_t mode);
+
+/* Measurement aid (not part of the method): gathers rows ids_dev[0..n_ids) (each in [0, n_rows), not
+ * checked) of rows_dev (row_bytes per row, multiple of 16, <= 512) with the search kernels' access
+ * pattern, rows_per_wave rows per wavefront, and writes one word per lane to out_dev
+ * (ceil(n_ids / rows_per_wave) * 64 uint32).  Asynchronous on `stream`.  Timing it gives the rate at
+ * which this GPU can serve the random row gathers the search performs. */
+int ggnn_gather_probe(const void* rows_dev, int64_t n_rows, int32_t row_bytes, const int32_t* ids_dev, int64_t n_ids,
+                      int32_t rows_per_wave, uint32_t* out_dev, void* stream);
 
 void ggnn_free(ggnn_graph* g);
 const char* ggnn_last_error(void);

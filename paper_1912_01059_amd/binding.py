@@ -45,7 +45,7 @@ EXPORTS = [
     "ggnn_build", "ggnn_build_ex", "ggnn_graph_create", "ggnn_select", "ggnn_merge", "ggnn_sym",
     "ggnn_build_steps", "ggnn_build_get_times", "ggnn_query", "ggnn_query_ex", "ggnn_graph_info",
     "ggnn_graph_export", "ggnn_graph_import", "ggnn_graph_export_dnn", "ggnn_graph_import_dnn",
-    "ggnn_graph_export_inv_count", "ggnn_set_cache_mode", "ggnn_free", "ggnn_last_error",
+    "ggnn_graph_export_inv_count", "ggnn_set_cache_mode", "ggnn_gather_probe", "ggnn_free", "ggnn_last_error",
 ]
 
 
@@ -75,6 +75,7 @@ def lib():
         L.ggnn_graph_import_dnn.argtypes = [vp, vp, f32, f32]
         L.ggnn_graph_export_inv_count.argtypes = [vp, i32, vp]
         L.ggnn_set_cache_mode.argtypes = [i32]
+        L.ggnn_gather_probe.argtypes = [vp, i64, i32, vp, i64, i32, vp, vp]
         L.ggnn_free.argtypes = [vp]
         L.ggnn_free.restype = None
         L.ggnn_last_error.restype = C.c_char_p
@@ -85,6 +86,18 @@ def lib():
 def set_cache_mode(mode: int) -> None:
     """0: best / prioq in registers when they fit (default); 1: always in LDS."""
     _check(lib().ggnn_set_cache_mode(mode))
+
+
+def gather_probe(rows, ids, rows_per_wave, out=None):
+    """ggnn_gather_probe on torch's current stream (asynchronous); returns the output tensor."""
+    import torch
+    n = ids.shape[0]
+    waves = (n + rows_per_wave - 1) // rows_per_wave
+    if out is None:
+        out = torch.empty(waves * 64, dtype=torch.int32, device=rows.device)
+    _check(lib().ggnn_gather_probe(_dev_ptr(rows), rows.shape[0], rows.shape[1] * rows.element_size(), _dev_ptr(ids), n,
+                                   rows_per_wave, _dev_ptr(out), C.c_void_p(torch.cuda.current_stream().cuda_stream)))
+    return out
 
 
 def last_error() -> str:

@@ -17,7 +17,7 @@ SOURCES = ["ggnn_search_reg.hip", "ggnn_search_lds.hip", "ggnn_build.hip", "ggnn
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument",
-         "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+         "-I", os.path.join(ROOT, "include"), "-I", CSRC] + os.environ.get("GGNN_EXTRA_FLAGS", "").split()
 
 
 def _hipcc() -> str:

@@ -223,6 +223,15 @@ extern "C" {
 
 const char* ggnn_last_error(void) { return g_err; }
 
+int ggnn_gather_probe(const void* rows_dev, int64_t n_rows, int32_t row_bytes, const int32_t* ids_dev, int64_t n_ids,
+                      int32_t rows_per_wave, uint32_t* out_dev, void* stream) {
+  if (!rows_dev || !ids_dev || !out_dev) return fail(GGNN_ERR_INVALID, "NULL device pointer");
+  if (row_bytes < 16 || row_bytes % 16 != 0 || row_bytes > 512) return fail(GGNN_ERR_INVALID, "row_bytes %d not a multiple of 16 in [16, 512]", row_bytes);
+  if (n_rows < 1 || n_ids < 1 || rows_per_wave < 1) return fail(GGNN_ERR_INVALID, "sizes must be positive");
+  HIP_TRY(launch_gather_probe(rows_dev, row_bytes, ids_dev, n_ids, rows_per_wave, out_dev, (hipStream_t)stream));
+  return GGNN_OK;
+}
+
 int ggnn_set_cache_mode(int32_t mode) {
   if (mode != 0 && mode != 1) return fail(GGNN_ERR_INVALID, "cache mode %d is neither 0 nor 1", mode);
   g_cache_mode = mode;

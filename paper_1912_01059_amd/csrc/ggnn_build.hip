@@ -288,6 +288,44 @@ __global__ void sym_apply_kernel(GraphDev G, int layer, SymBuffers sb, int32_t* 
   inv_count[p] = nl;
 }
 
+// Measurement aid: reads rows ids[0..n) of `rows` with the access pattern of the search kernels
+// (8 lanes x 16 bytes per row, 8 rows per wave instruction, 24 rows in flight per wavefront) and
+// folds them into one word per wavefront, so that only the gather itself is timed.
+__global__ __launch_bounds__(kWave) void gather_probe_kernel(const uint8_t* __restrict__ rows, int row_bytes,
+                                                             const int32_t* __restrict__ ids, int64_t n,
+                                                             int rows_per_wave, uint32_t* __restrict__ out) {
+  const int lane = threadIdx.x, sub = lane & (kRowLanes - 1), grp = lane / kRowLanes;
+  const int nchunks = row_bytes / 16;
+  const int64_t first = (int64_t)blockIdx.x * rows_per_wave;
+  uint32_t acc = 0;
+  for (int r0 = 0; r0 < rows_per_wave; r0 += 3 * kRowsPerPass) {
+    uint4 v[3][4];
+#pragma unroll
+    for (int ps = 0; ps < 3; ps++) {
+      const int64_t i = first + r0 + ps * kRowsPerPass + grp;
+      const bool act = (r0 + ps * kRowsPerPass + grp) < rows_per_wave && i < n;
+      const uint8_t* ptr = rows + (size_t)(act ? ids[i] : 0) * (size_t)row_bytes;
+#pragma unroll
+      for (int ch = 0; ch < 4; ch++) {
+        const int chunk = ch * kRowLanes + sub;
+        v[ps][ch] = make_uint4(0, 0, 0, 0);
+        if (act && chunk < nchunks) v[ps][ch] = *(const uint4*)(ptr + (size_t)chunk * 16);
+      }
+    }
+#pragma unroll
+    for (int ps = 0; ps < 3; ps++)
+#pragma unroll
+      for (int ch = 0; ch < 4; ch++) acc ^= v[ps][ch].x ^ v[ps][ch].y ^ v[ps][ch].z ^ v[ps][ch].w;
+  }
+  out[(size_t)blockIdx.x * kWave + lane] = acc;
+}
+hipError_t launch_gather_probe(const void* rows, int row_bytes, const int32_t* ids, int64_t n, int rows_per_wave,
+                               uint32_t* out, hipStream_t stream) {
+  const int64_t waves = (n + rows_per_wave - 1) / rows_per_wave;
+  gather_probe_kernel<<<(unsigned)waves, kWave, 0, stream>>>((const uint8_t*)rows, row_bytes, ids, n, rows_per_wave, out);
+  return hipGetLastError();
+}
+
 static inline unsigned blocks_for(int64_t n) { return (unsigned)((n + 255) / 256); }
 
 hipError_t launch_sym_propose(const GraphDev& G, int layer, const SymBuffers& sb, int B, hipStream_t stream);

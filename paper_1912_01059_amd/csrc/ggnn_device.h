@@ -428,6 +428,9 @@ struct LdsCache {
     cache_fetch<DT, NCH, METRIC, PASSES>(c, G, layer, p, q, excl_row);
   }
   __device__ int32_t pop() { return cache_pop(c); }
+  __device__ int32_t pop_head() { return cache_pop(c); }
+  __device__ void mark_visited(int32_t) {}
+  __device__ int32_t next_head() const { return c.np > 0 ? key_id(c.pq[0]) : -1; }
   __device__ void transform(const int32_t* __restrict__ table) { cache_transform(c, table); }
   __device__ int32_t count() const { return c.nb; }
   __device__ float first_d() const { return c.d_first; }

@@ -5,6 +5,10 @@
 // were evaluated and rejected: the threshold of Eq. 2 never grows during a search on one layer,
 // so a point rejected once is rejected whenever it is proposed again, and skipping it changes no
 // result (rejected entries may be left out when the table fills up; visited entries never are).
+// Whether a proposal already sits in best or prioq is decided exactly by comparing it with the
+// entry every lane holds; a bit map in LDS (one bit per hash bucket, set when an id of that bucket
+// enters a list and cleared only when the layer changes) first rules out the many proposals
+// that cannot be listed.
 #pragma once
 #include "ggnn_device.h"
 
@@ -29,38 +33,89 @@ __device__ __forceinline__ u64 read_lane_u64(u64 v, int lane) {
   return ((u64)hi << 32) | lo;
 }
 
+#ifdef GGNN_PHASE_TIMING
+// Debug build only: cycles spent per phase of an iteration, summed over all wavefronts.
+__device__ unsigned long long g_phase_cycles[16];
+#define GGNN_T0() unsigned long long t_ph = __builtin_readcyclecounter()
+#define GGNN_TICK(i)                                             \
+  do {                                                           \
+    unsigned long long t_now = __builtin_readcyclecounter();     \
+    ph[i] += (uint32_t)(t_now - t_ph);                           \
+    t_ph = t_now;                                                \
+  } while (0)
+#else
+#define GGNN_T0()
+#define GGNN_TICK(i)
+#endif
+
 struct RegCache {
   static constexpr bool kInRegisters = true;
+#ifdef GGNN_PHASE_TIMING
+  uint32_t ph[12] = {0};
+  __device__ void flush_phases() {
+    if (lane_id() == 0)
+      for (int i = 0; i < 12; i++) atomicAdd(&g_phase_cycles[i], (unsigned long long)ph[i]);
+  }
+#endif
   u64 best, pq;                 // lane i: entry i, kEmptyKey beyond the fill level / capacity
   int32_t B, P, nb, np;
   int32_t iter, max_iter;
-  float tau, dnn, radius;
+  float tau, dnn, radius, d1, dk;
+  u64 last_best;                 // key of best[B-1]
   int32_t* hash; int32_t hmask;  // LDS: visited ids, and rejected ids with the top bit set
+  uint32_t* listed_bits;         // LDS: kListedBuckets bits
   int32_t nrej, rej_cap;
   u64* stage;                    // LDS: 4 x 64 keys for Transform
   int32_t* surv_id; int32_t* surv_row; float* surv_d;  // LDS, 64 each
   uint32_t pops, evals, gathers;
 
-  // hash slots: 4 per possible visited id (half of the table is the most ever occupied)
+  static constexpr int kListedBuckets = 8192;
+  // Hash slots: room for every visited id plus at least 128 rejected ids at a load of one half;
+  // 1024 slots (4 KB) when that suffices, so that five wavefronts per SIMD fit into the LDS.
   __host__ __device__ static int hash_slots(int max_iter) {
-    int h = 64;
-    while (h < 4 * max_iter) h <<= 1;
+    int h = 1024;
+    while (h < 2 * max_iter + 256) h <<= 1;
     return h;
   }
+  // the staging area of Transform (4 x 64 keys) shares its memory with the hash table, which
+  // Transform empties anyway
+  __host__ __device__ static size_t hash_bytes(const SearchParams& sp) {
+    const size_t h = (size_t)hash_slots(sp.max_iter) * 4;
+    return h > 4 * 64 * 8 ? h : 4 * 64 * 8;
+  }
   __host__ __device__ static size_t lds_bytes(const SearchParams& sp) {
-    return (size_t)hash_slots(sp.max_iter) * 4 + 4 * 64 * 8 + 3 * 64 * 4;
+    return hash_bytes(sp) + 3 * 64 * 4 + kListedBuckets / 8;
   }
 
   __device__ void bind(unsigned char* lds, const SearchParams& sp) {
     B = sp.B; P = sp.P; max_iter = sp.max_iter; tau = sp.tau; dnn = sp.dnn;
     const int H = hash_slots(sp.max_iter);
     stage = (u64*)lds;
-    hash = (int32_t*)(stage + 4 * 64);
+    hash = (int32_t*)lds;
     hmask = H - 1;
-    surv_id = hash + H;
+    surv_id = (int32_t*)(lds + hash_bytes(sp));
     surv_row = surv_id + 64;
     surv_d = (float*)(surv_row + 64);
+    listed_bits = (uint32_t*)(surv_d + 64);
     rej_cap = H / 2 - sp.max_iter;
+  }
+  // ---- which ids may be in best or prioq: one bit per bucket (a zero bit rules a proposal out)
+  __device__ __forceinline__ static uint32_t listed_bucket(int32_t id) {
+    return (mix32((uint32_t)id) >> 16) & (uint32_t)(kListedBuckets - 1);
+  }
+  __device__ void listed_clear() {
+    for (int i = lane_id(); i < kListedBuckets / 32; i += kWave) listed_bits[i] = 0;
+    wave_sync();
+  }
+  __device__ __forceinline__ void listed_add(int32_t id) {  // uniform call
+    if (lane_id() == 0) {
+      const uint32_t h = listed_bucket(id);
+      atomicOr(&listed_bits[h >> 5], 1u << (h & 31));
+    }
+  }
+  __device__ __forceinline__ bool maybe_listed(int32_t id) const {
+    const uint32_t h = listed_bucket(id);
+    return (listed_bits[h >> 5] >> (h & 31)) & 1u;
   }
   __device__ void clear_hash() {
     for (int i = lane_id(); i <= hmask; i += kWave) hash[i] = -1;
@@ -71,7 +126,8 @@ struct RegCache {
   __device__ void init() {
     best = pq = kEmptyKey;
     nb = np = 0; iter = 0; pops = evals = gathers = 0;
-    radius = INFINITY;
+    radius = INFINITY; d1 = dk = INFINITY; last_best = kEmptyKey;
+    listed_clear();
     clear_hash();
   }
   __device__ void set_radius(float r) { radius = r; }
@@ -105,19 +161,21 @@ struct RegCache {
     wave_sync();
   }
 
-  __device__ float first_d() const { return key_d(read_lane_u64(best, 0)); }
+  __device__ float first_d() const { return d1; }
   __device__ int32_t count() const { return nb; }
   __device__ uint32_t n_pops() const { return pops; }
   __device__ uint32_t n_evals() const { return evals; }
   __device__ uint32_t n_gathers() const { return gathers; }
-  // Eq. 2
+  // Eq. 2; d1 / dk are best[0].d and best[B-1].d (+inf while best is not full)
   __device__ float thr() const {
     if (nb == 0) return INFINITY;
-    const float d1 = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(best >> 32), 0));
-    const float dk = (nb < B) ? INFINITY
-                              : __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(best >> 32), B - 1));
     const float xi = tau * fminf(d1, dnn);
     return dk + xi;
+  }
+  __device__ void refresh_bounds() {
+    d1 = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(best >> 32), 0));
+    last_best = read_lane_u64(best, B - 1);  // all ones while best is not full
+    dk = (nb < B) ? INFINITY : key_d(last_best);
   }
 
   // sorted insertion into a register list; entries beyond `cap` fall off
@@ -130,24 +188,36 @@ struct RegCache {
     if (lane >= cap) L = kEmptyKey;
     if (pos < cap && n < cap) n++;
   }
-  // Alg. 2 Push
+  // Alg. 2 Push (the key is known not to be in either list).  Most accepted candidates lie
+  // between the k-th best distance and the threshold: they enter prioq only, so best (and the
+  // bounds derived from it) is touched only when the key really belongs there.
   __device__ void push(u64 key) {
-    list_insert(best, nb, B, key);
+    if (nb < B || key < last_best) {
+      list_insert(best, nb, B, key);
+      refresh_bounds();
+    }
     list_insert(pq, np, P, key);
+    listed_add(key_id(key));
   }
 
-  // Alg. 2 Pop
-  __device__ int32_t pop() {
+  // Alg. 2 Pop, first half: take the head off prioq (or -1 when the search on this layer ends).
+  // The caller completes the pop with mark_visited(id) once the adjacency load is under way.
+  __device__ int32_t pop_head() {
     if (np == 0 || iter >= max_iter) return -1;
     const u64 head = read_lane_u64(pq, 0);
     const float d = key_d(head);
     if (!(d <= thr() && d <= radius)) return -1;
     pq = wave_shift_down(pq, kEmptyKey);
     np--;
-    const int32_t id = key_id(head);
-    insert_visited(id);
     iter++;
     pops++;
+    return key_id(head);
+  }
+  __device__ void mark_visited(int32_t id) { insert_visited(id); }
+  __device__ int32_t next_head() const { return np > 0 ? key_id(read_lane_u64(pq, 0)) : -1; }
+  __device__ int32_t pop() {
+    const int32_t id = pop_head();
+    if (id >= 0) mark_visited(id);
     return id;
   }
 
@@ -189,6 +259,16 @@ struct RegCache {
     np = m < P ? m : P;
     pq = (lane < np) ? out[lane] : kEmptyKey;
     iter = 0;
+    if (nb > 0) refresh_bounds();
+    listed_clear();
+    if (lane < nb) {
+      const uint32_t h = listed_bucket(key_id(best));
+      atomicOr(&listed_bits[h >> 5], 1u << (h & 31));
+    }
+    if (lane < np) {
+      const uint32_t h = listed_bucket(key_id(pq));
+      atomicOr(&listed_bits[h >> 5], 1u << (h & 31));
+    }
     clear_hash();
   }
 
@@ -196,29 +276,33 @@ struct RegCache {
   template <int DT, int NCH, int METRIC, int PASSES>
   __device__ void fetch(const GraphDev& G, int layer, int32_t p, const QueryRegs<DT, NCH>& q, int32_t excl_row) {
     const int lane = lane_id();
+    GGNN_T0();
     bool alive = p >= 0;
     int32_t row = -1;
     if (alive) {
       row = (layer == 0) ? p : G.to_base[layer][p];
       alive = row != excl_row;
     }
+    GGNN_TICK(1);  // adjacency row arrives
     bool seen_rejected = false;
     if (alive) {
       const int kind = probe(p);
       alive = kind == 0;
       seen_rejected = kind == 2;
     }
-    // membership in best / prioq: one broadcast per remaining proposal
-    u64 cand = __ballot(alive);
+    GGNN_TICK(2);  // hash probe
+    // membership in best / prioq: only proposals whose bucket bit is set can be listed;
+    // each of those is broadcast and compared with the entry every lane holds
+    u64 cand = __ballot(alive && maybe_listed(p));
     u64 known = 0;
     while (cand) {
       const int j = __builtin_ctzll(cand);
       cand &= cand - 1;
       const int32_t pid = __builtin_amdgcn_readlane(p, j);
-      const bool hit = key_id(best) == pid || key_id(pq) == pid;
-      if (__ballot(hit)) known |= 1ull << j;
+      if (__ballot(key_id(best) == pid || key_id(pq) == pid)) known |= 1ull << j;
     }
     alive = alive && !((known >> lane) & 1);
+    GGNN_TICK(3);  // membership in best / prioq
     const u64 mask = __ballot(alive);
     const int ns = __popcll(mask);
     // a point rejected before would be evaluated and rejected again: counted, not gathered
@@ -231,6 +315,7 @@ struct RegCache {
       surv_row[r] = row;
     }
     wave_sync();
+    GGNN_TICK(4);  // compaction
     const int sub = lane & (kRowLanes - 1), grp = lane / kRowLanes;
     for (int b0 = 0; b0 < ns; b0 += kRowsPerPass * PASSES) {
       uint4 raw[PASSES][NCH];
@@ -256,6 +341,7 @@ struct RegCache {
       }
     }
     wave_sync();
+    GGNN_TICK(5);  // gather + distances
     // Survivors are pushed in list order with the threshold re-evaluated after every push.  The
     // threshold only shrinks, so whoever fails the threshold as it stands now fails later too:
     // only the others go through the sequential loop.
@@ -268,12 +354,19 @@ struct RegCache {
       const int r = __builtin_ctzll(todo);
       todo &= todo - 1;
       const float dr = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(d), r));
+#ifdef GGNN_PHASE_TIMING
+      ph[8]++;
+      if (dr <= thr()) ph[9]++;
+      ph[10] += (uint32_t)ns;
+#endif
       if (dr <= thr()) {
         push(make_key(dr, __builtin_amdgcn_readlane(id, r)));
         accepted |= 1ull << r;
       }
     }
+    GGNN_TICK(6);  // acceptance loop and pushes
     insert_rejected(mine && !((accepted >> lane) & 1), id);
+    GGNN_TICK(7);  // rejected filter
   }
 
   // results

@@ -8,7 +8,10 @@
 
 namespace ggnn {
 
-constexpr int kPasses = 3;  // 8 rows per pass: up to 24 rows in flight per wavefront
+#ifndef GGNN_PASSES
+#define GGNN_PASSES 2
+#endif
+constexpr int kPasses = GGNN_PASSES;  // 8 rows per pass: up to 8*kPasses rows in flight per wavefront
 
 template <int DT, int NCH>
 __device__ inline void normalise_query(QueryRegs<DT, NCH>& q) {
@@ -24,14 +27,24 @@ __device__ inline void normalise_query(QueryRegs<DT, NCH>& q) {
   }
 }
 
-// Alg. 1 main loop on one layer
+// Alg. 1 main loop on one layer.  The adjacency row of the point most likely to be popped next
+// (the head prioq is left with) is requested one iteration ahead; it is used if that point is
+// indeed popped next, otherwise the row is loaded as usual.
 template <class C, int DT, int NCH, int METRIC>
 __device__ inline void descend(C& c, const GraphDev& G, int layer, const QueryRegs<DT, NCH>& q, int32_t excl_row) {
   const int lane = lane_id();
   const int32_t* __restrict__ E = G.edges[layer];
+  int32_t ahead_id = -1, ahead_row = -1;
   int32_t a;
-  while ((a = c.pop()) >= 0) {
-    const int32_t p = (lane < G.K) ? E[(size_t)a * G.K + lane] : -1;
+  while ((a = c.pop_head()) >= 0) {
+    int32_t p;
+    if (a == ahead_id) p = ahead_row;
+    else p = (lane < G.K) ? E[(size_t)a * G.K + lane] : -1;
+#ifndef GGNN_NO_PREFETCH
+    ahead_id = c.next_head();
+    ahead_row = (ahead_id >= 0 && lane < G.K) ? E[(size_t)ahead_id * G.K + lane] : -1;
+#endif
+    c.mark_visited(a);
     c.template fetch<DT, NCH, METRIC, kPasses>(G, layer, p, q, excl_row);
   }
 }
@@ -63,6 +76,9 @@ __global__ __launch_bounds__(kWave) void query_kernel(GraphDev G, const uint8_t*
     descend<C, DT, NCH, METRIC>(c, G, 0, q, -1);
   }
   c.store_results(k, ids + (size_t)qi * k, dists + (size_t)qi * k);
+#ifdef GGNN_PHASE_TIMING
+  if constexpr (C::kInRegisters) c.flush_phases();
+#endif
   if (counters && lane == 0) {
     counters[4 * qi + 0] = c.n_pops();
     counters[4 * qi + 1] = c.n_evals();

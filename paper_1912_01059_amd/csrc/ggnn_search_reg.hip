@@ -15,4 +15,16 @@ hipError_t launch_sym_search_reg(const GraphDev& G, int dtype, int metric, int l
                                  const SearchParams& sp, const SymBuffers& sb, hipStream_t stream) {
   return launch_sym_search_t<RegCache>(G, dtype, metric, layer, round, w_mid, sp, sb, stream);
 }
+#ifdef GGNN_PHASE_TIMING
+hipError_t read_phase_cycles(unsigned long long* out16, int reset) {
+  hipError_t e = hipMemcpyFromSymbol(out16, HIP_SYMBOL(g_phase_cycles), sizeof(unsigned long long) * 16);
+  if (e != hipSuccess) return e;
+  if (reset) {
+    unsigned long long z[16] = {0};
+    e = hipMemcpyToSymbol(HIP_SYMBOL(g_phase_cycles), z, sizeof(z));
+  }
+  return e;
+}
+extern "C" int ggnn_debug_phase_cycles(unsigned long long* out16, int reset) { return (int)read_phase_cycles(out16, reset); }
+#endif
 }  // namespace ggnn
