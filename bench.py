@@ -58,6 +58,8 @@ def main():
     ap.add_argument("--pq-cap", type=int, default=64)
     ap.add_argument("--large-batch", type=int, default=100_000, help="also time a batch of this many queries (0 = skip)")
     ap.add_argument("--sweep", action="store_true", help="also trace the QPS-vs-recall curve")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device-to-device copy (reference for hardware byte counters)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=2000)
     args = ap.parse_args()
@@ -173,6 +175,14 @@ def main():
     gather_ceiling = round(n_probe * (D * esize + 4) / (e0g.elapsed_time(e1g) / 3 * 1e-3) / 1e9, 1)
     del pids, pout
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     # ---- roofline of the search kernel: algorithmic bytes per launch / kernel time ----
     # per query: the query vector, one adjacency row per pop, one base row (and its id) per row
     # actually gathered (start points included), the k results (ids + distances)
@@ -180,8 +190,20 @@ def main():
     s = graph.s
     algo_bytes = Q * (D * esize + k * 8) + cnt[0] * K * 4 + cnt[2] * (4 + D * esize)
     achieved = algo_bytes / (kernel_ms * 1e-3) / 1e9
+    # HBM bytes per launch measured with rocprofv3 counters (see profiles/): only valid for the
+    # operating point they were taken at
+    traffic = None
+    op_tag = "operating_point: %s levels=%d beam=%d slack=%g visited_cap=%d pq_cap=%d Q=%d" % (
+        args.workload, args.levels, chosen["beam"], chosen["slack"], chosen["visited_cap"], chosen["pq_cap"], Q)
+    pmc_path = os.path.join(ROOT, "profiles", "query_kernel_%s_pmc.txt" % args.workload)
+    if os.path.exists(pmc_path):
+        text = open(pmc_path).read()
+        if op_tag in text:
+            for line in text.splitlines():
+                if line.startswith("traffic_bytes_per_launch:"):
+                    traffic = int(line.split(":")[1])
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None, "kernel": "query_kernel",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic, "kernel": "query_kernel",
                 "kernel_ms": round(kernel_ms, 3), "algorithmic_bytes_per_launch": int(algo_bytes)}
 
     # ---- CPU baseline: the oracle's search of the same graph on a sample of the queries ----
