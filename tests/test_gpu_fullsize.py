@@ -1,0 +1,100 @@
+"""Full-size GPU check: the 1M x 128 benchmark workload in the launch configuration bench.py times.
+
+The oracle cannot build a 1M-point graph in test time, so the graph is built by the library (its
+builder is proven equal to the oracle's on the 10k configuration in test_gpu_parity.py); the
+library's search of that graph is then compared with the oracle's search of the same graph on
+sampled queries, and with exhaustive search; properties that hold at any size are checked on all
+of the output."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def workload():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import ggnn_inputs
+    import paper_1912_01059_amd as ggnn
+    ggnn.set_cache_mode(0)
+    base, queries, cfg = ggnn_inputs.make("sift1m")
+    b = torch.from_numpy(base).cuda()
+    q = torch.from_numpy(queries).cuda()
+    g = ggnn.build(b, cfg["K"], 3, seed=42)
+    return ggnn, base, queries, cfg, b, q, g
+
+
+OP = dict(k=10, beam=10, slack=0.05, visited_cap=64, pq_cap=64, every_layer=True)  # bench.py's operating point
+
+
+def test_graph_invariants_at_full_size(workload):
+    ggnn, base, queries, cfg, b, q, g = workload
+    K = cfg["K"]
+    assert g.n == [1_000_000, 5664, 32] and g.g == 177
+    for l in range(g.L):
+        e, tl, tb = g.export_layer(l)
+        n = g.n[l]
+        assert e.shape == (n, K)
+        assert (e >= 0).all() and (e < n).all()
+        srt = np.sort(e, axis=1)
+        assert (np.diff(srt, axis=1) > 0).all(), "repeated id in a row of layer %d" % l
+        assert not (e == np.arange(n)[:, None]).any(), "self loop on layer %d" % l
+        if l >= 1:
+            assert len(np.unique(tb)) == n and tb.min() >= 0 and tb.max() < 1_000_000
+    _, tl1, tb1 = g.export_layer(1)
+    _, tl2, tb2 = g.export_layer(2)
+    assert np.array_equal(tl1, tb1) and np.array_equal(tb2, tb1[tl2])
+    assert g.export_inv_count(0).max() <= K - K // 2
+    d, mean, mx = g.export_dnn()
+    assert mx == d.max() and abs(mean - d.astype(np.float64).mean()) <= 1e-6 * mean
+    # d_nn1 is the true distance to the first neighbour found by the last merge (Eq. 3, Eq. 4), and
+    # the first K/2 entries of a row are merge results in ascending order
+    e0, _, _ = g.export_layer(0)
+    rows = np.arange(0, 1_000_000, 997)
+    d2 = ((base[rows][:, None, :].astype(np.int64) - base[e0[rows, : K // 2]].astype(np.int64)) ** 2).sum(2)
+    assert (np.diff(d2, axis=1) >= 0).all()
+    assert np.array_equal(np.sqrt(d2[:, 0].astype(np.float32)), d[rows])
+
+
+def test_search_properties_and_sampled_parity_at_full_size(workload):
+    from oracle import ggnn_ref as R
+    ggnn, base, queries, cfg, b, q, g = workload
+    k = OP["k"]
+    ids, dists, cnt = g.query(q, k, OP["beam"], OP["slack"], pq_cap=OP["pq_cap"], visited_cap=OP["visited_cap"],
+                              every_layer=True, counters=True)
+    ids, dists, cnt = ids.cpu().numpy(), dists.cpu().numpy(), cnt.cpu().numpy()
+    # properties of every result row
+    assert (ids >= 0).all() and (ids < 1_000_000).all()
+    assert (np.diff(np.sort(ids, axis=1), axis=1) > 0).all()             # distinct
+    key = dists.astype(np.float64) * 2 ** 32 + ids                       # order (distance, id)
+    assert (np.diff(key, axis=1) > 0).all()
+    assert cnt[:, 0].max() <= 2 * OP["visited_cap"]                      # iteration limit per layer, 2 layers searched
+    # every reported distance is the true one (integer-valued data: exact)
+    sample = np.arange(0, len(queries), 50)
+    for i in sample:
+        d2 = ((base[ids[i]].astype(np.int64) - queries[i].astype(np.int64)) ** 2).sum(1)
+        assert np.array_equal(dists[i], np.sqrt(d2.astype(np.float32)))
+    # the oracle's search of the same graph, query by query
+    og = R.Graph(base, cfg["K"], 3, seed=42)
+    for l in range(g.L):
+        e, tl, tb = g.export_layer(l)
+        og.edges(l)[:] = e
+        if l >= 1:
+            og.to_lower(l)[:] = tl
+            og.to_base(l)[:] = tb
+    _, mean, mx = g.export_dnn()
+    og.stats()[:] = (mean, mx)
+    rids, rd, rcnt = og.query(queries[sample], k, OP["beam"], OP["slack"], pq_cap=OP["pq_cap"],
+                              visited_cap=OP["visited_cap"], every_layer=True, counters=True)
+    assert np.array_equal(ids[sample], rids)
+    assert np.array_equal(dists[sample].view(np.uint32), rd.view(np.uint32))
+    assert np.array_equal(cnt[sample][:, :2].astype(np.uint32), rcnt)
+    # recall against exhaustive search (oracle), on a sub-sample; the library's answers being the
+    # oracle's, its recall is the oracle's
+    sub = sample[:64]
+    gt, gt_d = R.bruteforce(base, queries[sub], k)
+    rec = R.recall(ids[sub], gt)
+    assert abs(rec - R.recall(rids[:64], gt)) <= 0.002
+    assert rec >= 0.93
