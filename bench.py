@@ -57,6 +57,8 @@ def main():
     ap.add_argument("--visited-cap", type=int, default=64, help="visited capacity = iteration limit per layer")
     ap.add_argument("--pq-cap", type=int, default=64)
     ap.add_argument("--large-batch", type=int, default=100_000, help="also time a batch of this many queries (0 = skip)")
+    ap.add_argument("--build-iter", type=int, default=192,
+                    help="visited capacity = iteration limit per layer of the construction searches")
     ap.add_argument("--sweep", action="store_true", help="also trace the QPS-vs-recall curve")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy (reference for hardware byte counters)")
@@ -88,7 +90,7 @@ def main():
     # ---- construction (timed once; the graph stays resident) ----
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    graph = ggnn.build(base, K, args.levels, seed=42, metric=metric)
+    graph = ggnn.build(base, K, args.levels, seed=42, metric=metric, visited_cap=args.build_iter, max_iter=args.build_iter)
     torch.cuda.synchronize()
     build_s = time.perf_counter() - t0
     phases = graph.times()
@@ -239,6 +241,8 @@ def main():
                    "visited_cap": chosen["visited_cap"], "descent": "every layer (Alg. 4)"},
         "recall_at_10": round(final_recall, 4),
         "build_seconds": round(build_s, 3),
+        "build_config": {"levels": args.levels, "K": K, "segment_size": graph.s, "tau_build": 0.5, "refinements": 2,
+                         "pq_cap": 64, "visited_cap": args.build_iter, "max_iter": args.build_iter},
         "build_phases_ms": {kk: round(v, 2) for kk, v in phases.items()},
         "graph_bytes": graph.graph_bytes,
         "pops_per_query": round(cnt[0] / Q, 1), "dist_evals_per_query": round(cnt[1] / Q, 1),

@@ -297,11 +297,20 @@ __device__ __forceinline__ void chunk_to_float(const uint4& v, float* out) {
   }
 }
 
-// butterfly over the 8 lanes that share a row
+// butterfly over the 8 lanes that share a row: lane l adds the value of lane l^4, then l^2, then
+// l^1.  Done with DPP moves (no LDS traffic): the l^4 exchange is a shift by four lanes within a
+// row of 16, to the right for the upper half of each group and to the left for the lower half
+// (bank masks 0xA / 0x5); the other two are quad permutations.
+template <int CTRL, int BANK_MASK>
+__device__ __forceinline__ float dpp_move(float old, float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(v), CTRL, 0xf, BANK_MASK, false));
+}
 __device__ __forceinline__ float row_reduce(float acc) {
-  acc = acc + __shfl_xor(acc, 4, kWave);
-  acc = acc + __shfl_xor(acc, 2, kWave);
-  acc = acc + __shfl_xor(acc, 1, kWave);
+  float t = dpp_move<0x114, 0xA>(0.0f, acc);  // row_shr:4 -> lanes 4..7 and 12..15 of each row
+  t = dpp_move<0x104, 0x5>(t, acc);           // row_shl:4 -> lanes 0..3 and 8..11
+  acc = acc + t;
+  acc = acc + dpp_move<0x4E, 0xF>(0.0f, acc);  // quad_perm [2,3,0,1]
+  acc = acc + dpp_move<0xB1, 0xF>(0.0f, acc);  // quad_perm [1,0,3,2]
   return acc;
 }
 
@@ -323,9 +332,9 @@ __device__ inline void load_query(QueryRegs<DT, NCH>& q, const uint8_t* row, int
   }
 }
 
-// one row against the query, METRIC 0: sqrt(sum (q-x)^2), 1: max(0, 1 - sum q*x)
+// one row against the query: METRIC 0: sum (q-x)^2, 1: sum q*x, in the fixed order
 template <int DT, int NCH, int METRIC>
-__device__ __forceinline__ float row_distance(const QueryRegs<DT, NCH>& q, const uint4 (&raw)[NCH]) {
+__device__ __forceinline__ float row_sum(const QueryRegs<DT, NCH>& q, const uint4 (&raw)[NCH]) {
   constexpr int E = Elem<DT>::per_chunk;
   float acc = 0.0f;
 #pragma unroll
@@ -342,9 +351,17 @@ __device__ __forceinline__ float row_distance(const QueryRegs<DT, NCH>& q, const
       }
     }
   }
-  acc = row_reduce(acc);
-  if (METRIC == 0) return __builtin_sqrtf(acc);
-  return fmaxf(0.0f, 1.0f - acc);
+  return row_reduce(acc);
+}
+// from the sum to the distance: METRIC 0: sqrt(sum), 1: max(0, 1 - sum)
+template <int METRIC>
+__device__ __forceinline__ float finish_distance(float sum) {
+  if (METRIC == 0) return __builtin_sqrtf(sum);
+  return fmaxf(0.0f, 1.0f - sum);
+}
+template <int DT, int NCH, int METRIC>
+__device__ __forceinline__ float row_distance(const QueryRegs<DT, NCH>& q, const uint4 (&raw)[NCH]) {
+  return finish_distance<METRIC>(row_sum<DT, NCH, METRIC>(q, raw));
 }
 
 // Alg. 2 Fetch.  Lane j holds proposal p (or -1).  Known points are dropped against the

@@ -60,9 +60,9 @@ struct RegCache {
   u64 best, pq;                 // lane i: entry i, kEmptyKey beyond the fill level / capacity
   int32_t B, P, nb, np;
   int32_t iter, max_iter;
-  float tau, dnn, radius, d1, dk;
+  float tau, dnn, radius, d1, dk, thr_now;
   u64 last_best;                 // key of best[B-1]
-  int32_t* hash; int32_t hmask;  // LDS: visited ids, and rejected ids with the top bit set
+  int32_t* hash; int32_t hmask, hshift;  // LDS: visited ids, and rejected ids with the top bit set
   uint32_t* listed_bits;         // LDS: kListedBuckets bits
   int32_t nrej, rej_cap;
   u64* stage;                    // LDS: 4 x 64 keys for Transform
@@ -93,6 +93,7 @@ struct RegCache {
     stage = (u64*)lds;
     hash = (int32_t*)lds;
     hmask = H - 1;
+    hshift = 32 - (31 - __builtin_clz((unsigned)H));
     surv_id = (int32_t*)(lds + hash_bytes(sp));
     surv_row = surv_id + 64;
     surv_d = (float*)(surv_row + 64);
@@ -100,9 +101,13 @@ struct RegCache {
     rej_cap = H / 2 - sp.max_iter;
   }
   // ---- which ids may be in best or prioq: one bit per bucket (a zero bit rules a proposal out)
+  // one multiplicative hash serves both tables: its top bits index the visited / rejected table,
+  // bits 6.. the bit map
+  __device__ __forceinline__ static uint32_t hash_of(int32_t id) { return (uint32_t)id * 0x9E3779B1u; }
   __device__ __forceinline__ static uint32_t listed_bucket(int32_t id) {
-    return (mix32((uint32_t)id) >> 16) & (uint32_t)(kListedBuckets - 1);
+    return (hash_of(id) >> 6) & (uint32_t)(kListedBuckets - 1);
   }
+  __device__ __forceinline__ uint32_t slot_of(int32_t id) const { return hash_of(id) >> hshift; }
   __device__ void listed_clear() {
     for (int i = lane_id(); i < kListedBuckets / 32; i += kWave) listed_bits[i] = 0;
     wave_sync();
@@ -126,7 +131,7 @@ struct RegCache {
   __device__ void init() {
     best = pq = kEmptyKey;
     nb = np = 0; iter = 0; pops = evals = gathers = 0;
-    radius = INFINITY; d1 = dk = INFINITY; last_best = kEmptyKey;
+    radius = INFINITY; d1 = dk = thr_now = INFINITY; last_best = kEmptyKey;
     listed_clear();
     clear_hash();
   }
@@ -134,7 +139,7 @@ struct RegCache {
 
   // 0: unknown, 1: visited, 2: evaluated before and rejected
   __device__ int probe(int32_t id) const {
-    uint32_t h = mix32((uint32_t)id) & (uint32_t)hmask;
+    uint32_t h = slot_of(id);
     int32_t v;
     while ((v = hash[h]) != -1) {
       if ((v & 0x7FFFFFFF) == id) return (v < 0) ? 2 : 1;
@@ -144,7 +149,7 @@ struct RegCache {
   }
   __device__ void insert_visited(int32_t id) {  // uniform call
     if (lane_id() == 0) {
-      uint32_t h = mix32((uint32_t)id) & (uint32_t)hmask;
+      uint32_t h = slot_of(id);
       while (hash[h] != -1) h = (h + 1) & (uint32_t)hmask;
       hash[h] = id;
     }
@@ -155,7 +160,7 @@ struct RegCache {
     if (cnt == 0 || nrej + cnt > rej_cap) return;
     nrej += cnt;
     if (mine) {
-      uint32_t h = mix32((uint32_t)id) & (uint32_t)hmask;
+      uint32_t h = slot_of(id);
       while (atomicCAS(&hash[h], -1, (int32_t)((uint32_t)id | 0x80000000u)) != -1) h = (h + 1) & (uint32_t)hmask;
     }
     wave_sync();
@@ -167,15 +172,13 @@ struct RegCache {
   __device__ uint32_t n_evals() const { return evals; }
   __device__ uint32_t n_gathers() const { return gathers; }
   // Eq. 2; d1 / dk are best[0].d and best[B-1].d (+inf while best is not full)
-  __device__ float thr() const {
-    if (nb == 0) return INFINITY;
-    const float xi = tau * fminf(d1, dnn);
-    return dk + xi;
-  }
+  __device__ float thr() const { return thr_now; }
   __device__ void refresh_bounds() {
     d1 = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(best >> 32), 0));
     last_best = read_lane_u64(best, B - 1);  // all ones while best is not full
     dk = (nb < B) ? INFINITY : key_d(last_best);
+    const float xi = tau * fminf(d1, dnn);
+    thr_now = (nb == 0) ? INFINITY : dk + xi;
   }
 
   // sorted insertion into a register list; entries beyond `cap` fall off
@@ -335,8 +338,8 @@ struct RegCache {
       for (int ps = 0; ps < PASSES; ps++) {
         if (b0 + ps * kRowsPerPass < ns) {  // uniform: skip passes without rows
           const int r = b0 + ps * kRowsPerPass + grp;
-          const float d = row_distance<DT, NCH, METRIC>(q, raw[ps]);
-          if (r < ns && sub == 0) surv_d[r] = d;
+          const float sum = row_sum<DT, NCH, METRIC>(q, raw[ps]);
+          if (r < ns && sub == 0) surv_d[r] = sum;
         }
       }
     }
@@ -346,7 +349,7 @@ struct RegCache {
     // threshold only shrinks, so whoever fails the threshold as it stands now fails later too:
     // only the others go through the sequential loop.
     const bool mine = lane < ns;
-    const float d = mine ? surv_d[lane] : INFINITY;
+    const float d = mine ? finish_distance<METRIC>(surv_d[lane]) : INFINITY;  // one sqrt for the whole fetch
     const int32_t id = mine ? surv_id[lane] : -1;
     u64 todo = __ballot(mine && d <= thr() && d <= radius);
     u64 accepted = 0;

@@ -27,23 +27,15 @@ __device__ inline void normalise_query(QueryRegs<DT, NCH>& q) {
   }
 }
 
-// Alg. 1 main loop on one layer.  The adjacency row of the point most likely to be popped next
-// (the head prioq is left with) is requested one iteration ahead; it is used if that point is
-// indeed popped next, otherwise the row is loaded as usual.
+// Alg. 1 main loop on one layer.  The popped point is entered into visited while its adjacency
+// row is on its way.
 template <class C, int DT, int NCH, int METRIC>
 __device__ inline void descend(C& c, const GraphDev& G, int layer, const QueryRegs<DT, NCH>& q, int32_t excl_row) {
   const int lane = lane_id();
   const int32_t* __restrict__ E = G.edges[layer];
-  int32_t ahead_id = -1, ahead_row = -1;
   int32_t a;
   while ((a = c.pop_head()) >= 0) {
-    int32_t p;
-    if (a == ahead_id) p = ahead_row;
-    else p = (lane < G.K) ? E[(size_t)a * G.K + lane] : -1;
-#ifndef GGNN_NO_PREFETCH
-    ahead_id = c.next_head();
-    ahead_row = (ahead_id >= 0 && lane < G.K) ? E[(size_t)ahead_id * G.K + lane] : -1;
-#endif
+    const int32_t p = (lane < G.K) ? E[(size_t)a * G.K + lane] : -1;
     c.mark_visited(a);
     c.template fetch<DT, NCH, METRIC, kPasses>(G, layer, p, q, excl_row);
   }
