@@ -1,0 +1,146 @@
+"""Reports around the hot path, on the synthetic workloads of ggnn_inputs (needs a GPU):
+
+  quality    for-all kNN quality of the built graph: C@1 / C@10 of the bottom-layer rows against
+             exhaustive search on a sample of points, and the build-time split (the paper's
+             'For-all Queries' table and construction-time composition)
+  refine     query recall / speed after r = 0..3 refinement passes (Alg. 6)
+  sym        symmetric-linking constraint on / off (Sec. 4.2.1)
+  tau_b      construction slack factor against build time and query speed at fixed recall
+  batch      queries per second against the number of queries in a batch
+
+Each report prints JSON lines.  Ground truth comes from an exhaustive search with torch (plumbing,
+not part of the library)."""
+from __future__ import annotations
+
+import argparse
+import json
+import time
+
+
+def exhaustive(torch, base, queries, k, cosine=False, chunk=500):
+    b, q = base.float(), queries.float()
+    if cosine:
+        b = b / b.norm(dim=1, keepdim=True)
+        q = q / q.norm(dim=1, keepdim=True)
+    bn = (b * b).sum(1)
+    ids, d = [], []
+    for lo in range(0, q.shape[0], chunk):
+        x = q[lo:lo + chunk]
+        dist = (1.0 - x @ b.T) if cosine else ((x * x).sum(1)[:, None] + bn[None, :] - 2.0 * (x @ b.T)).clamp_min(0).sqrt()
+        v, i = torch.topk(dist, k, dim=1, largest=False)
+        ids.append(i)
+        d.append(v)
+    return torch.cat(ids), torch.cat(d)
+
+
+def recall(dists, gt_d, rel=2e-5):
+    k = gt_d.shape[1]
+    tol = gt_d[:, k - 1:k] * (1.0 + rel) + 1e-7
+    return float(((dists <= tol).sum(1).clamp(max=k).float().mean() / k).item())
+
+
+def timed_query(torch, g, q, k, beam, slack, limit, every_layer, reps=3):
+    ids, d, cnt = g.query(q, k, beam, slack, visited_cap=limit, max_iter=limit, every_layer=every_layer, counters=True)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        g.query(q, k, beam, slack, visited_cap=limit, max_iter=limit, every_layer=every_layer, out=(ids, d), asynchronous=True)
+    e1.record()
+    torch.cuda.synchronize()
+    return d, cnt, e0.elapsed_time(e1) / reps
+
+
+def graph_quality(torch, g, base, cosine, step):
+    sample = torch.arange(0, base.shape[0], step, device=base.device)
+    gt, _ = exhaustive(torch, base, base[sample], 11, cosine)
+    rows = torch.from_numpy(g.export_layer(0)[0]).to(base.device)[sample]
+    knn = g.K // 2
+    c1 = (rows[:, 0] == gt[:, 1]).float().mean().item()
+    hit = (rows[:, :knn, None] == gt[:, None, 1:11]).any(2).sum(1).float()
+    return {"sample": int(sample.numel()), "C@1": round(c1, 4), "C@10": round(float((hit.clamp(max=10) / 10).mean()), 4)}
+
+
+def main():
+    import torch
+
+    import ggnn_inputs
+    import paper_1912_01059_amd as ggnn
+
+    ap = argparse.ArgumentParser()
+    ap.add_argument("report", choices=["quality", "refine", "sym", "tau_b", "batch"])
+    ap.add_argument("--workload", default="sift1m")
+    ap.add_argument("--n", type=int, default=None)
+    ap.add_argument("--levels", type=int, default=3)
+    ap.add_argument("--build-iter", type=int, default=192)
+    ap.add_argument("--slack", type=float, default=0.05)
+    ap.add_argument("--beam", type=int, default=10)
+    ap.add_argument("--limit", type=int, default=64)
+    ap.add_argument("--direct", action="store_true", help="drop from the top layer straight to the bottom one")
+    a = ap.parse_args()
+
+    base_np, queries_np, cfg = ggnn_inputs.make(a.workload, n=a.n)
+    dev = torch.device("cuda:0")
+    base, q = torch.from_numpy(base_np).to(dev), torch.from_numpy(queries_np).to(dev)
+    cosine = cfg["metric"] == "cosine"
+    metric = ggnn.COSINE if cosine else ggnn.L2
+    k, K = cfg["k"], cfg["K"]
+    _, gt_d = exhaustive(torch, base, q, k, cosine)
+    every = not a.direct
+
+    def build(**kw):
+        args = dict(seed=42, metric=metric, visited_cap=a.build_iter, max_iter=a.build_iter)
+        args.update(kw)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        g = ggnn.build(base, K, a.levels, **args)
+        torch.cuda.synchronize()
+        return g, time.perf_counter() - t0
+
+    def query_line(g):
+        d, cnt, ms = timed_query(torch, g, q, k, a.beam, a.slack, a.limit, every)
+        c = cnt.double().mean(0).tolist()
+        return {"recall": round(recall(d, gt_d), 4), "qps": round(q.shape[0] / ms * 1e3), "pops": round(c[0], 1),
+                "rows_gathered": round(c[2], 1)}
+
+    if a.report == "quality":
+        g, secs = build()
+        out = {"report": "quality", "workload": a.workload, "levels": a.levels, "build_seconds": round(secs, 3),
+               "phases_ms": {kk: round(v, 2) for kk, v in g.times().items()}}
+        t = g.times()
+        tot = t["merge_ms"] + t["sym_ms"] + t["select_ms"] + t["stats_ms"]
+        out["split_percent"] = {kk[:-3]: round(100.0 * t[kk] / tot, 2) for kk in ("merge_ms", "sym_ms", "select_ms", "stats_ms")}
+        out["graph"] = graph_quality(torch, g, base, cosine, max(1, base.shape[0] // 2000))
+        out["inverse_links_per_row"] = round(float(g.export_inv_count(0).mean()), 3)
+        out["query"] = query_line(g)
+        print(json.dumps(out))
+    elif a.report == "refine":
+        for r in (0, 1, 2, 3):
+            g, secs = build(refinements=r)
+            print(json.dumps(dict(report="refine", refinements=r, build_seconds=round(secs, 3),
+                                  graph=graph_quality(torch, g, base, cosine, max(1, base.shape[0] // 2000)), **query_line(g))))
+            del g
+    elif a.report == "sym":
+        for on in (True, False):
+            g, secs = build(sym_constraint=on)
+            print(json.dumps(dict(report="sym", constraint=on, build_seconds=round(secs, 3),
+                                  inverse_links_per_row=round(float(g.export_inv_count(0).mean()), 3),
+                                  phases_ms={kk: round(v, 2) for kk, v in g.times().items()}, **query_line(g))))
+            del g
+    elif a.report == "tau_b":
+        for tb in (0.1, 0.2, 0.3, 0.5, 0.8):
+            g, secs = build(tau_build=tb, refinements=-1 if False else 2)
+            print(json.dumps(dict(report="tau_b", tau_build=tb, build_seconds=round(secs, 3),
+                                  graph=graph_quality(torch, g, base, cosine, max(1, base.shape[0] // 2000)), **query_line(g))))
+            del g
+    elif a.report == "batch":
+        g, secs = build()
+        import numpy as np
+        reps = -(-200_000 // q.shape[0])
+        big = q.repeat(reps, 1)[torch.randperm(q.shape[0] * reps, device=dev)].contiguous()
+        for n in (100, 300, 1000, 3000, 10_000, 30_000, 100_000, 200_000):
+            d, cnt, ms = timed_query(torch, g, big[:n].contiguous(), k, a.beam, a.slack, a.limit, every)
+            print(json.dumps(dict(report="batch", queries=n, kernel_ms=round(ms, 4), qps=round(n / ms * 1e3))))
+
+
+if __name__ == "__main__":
+    main()
