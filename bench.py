@@ -95,6 +95,15 @@ def main():
     build_s = time.perf_counter() - t0
     phases = graph.times()
 
+    # roofline of the construction's dominant kernel (merge_kernel): adjacency rows and base rows
+    # its searches read, plus the query row and the K results of every search, over the merge time
+    n_search = sum(graph.n[l] for l in range(graph.L))  # lower bound on the searches launched
+    merge_bytes = phases["merge_pops"] * K * 4 + phases["merge_rows"] * (4 + D * esize)
+    build_roofline = {"kernel": "merge_kernel", "bound": "hbm", "unit": "GB/s", "peak": HBM_PEAK_GBS,
+                      "achieved": round(merge_bytes / (phases["merge_ms"] * 1e-3) / 1e9, 1),
+                      "frac": round(merge_bytes / (phases["merge_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                      "pops": int(phases["merge_pops"]), "rows_gathered": int(phases["merge_rows"])}
+
     gt_ids, gt_d = ground_truth(torch, base, queries, k)
 
     # ---- operating point (found with --sweep; the default is the cheapest one that reaches
@@ -243,7 +252,8 @@ def main():
         "build_seconds": round(build_s, 3),
         "build_config": {"levels": args.levels, "K": K, "segment_size": graph.s, "tau_build": 0.5, "refinements": 2,
                          "pq_cap": 64, "visited_cap": args.build_iter, "max_iter": args.build_iter},
-        "build_phases_ms": {kk: round(v, 2) for kk, v in phases.items()},
+        "build_phases_ms": {kk: round(v, 2) for kk, v in phases.items() if kk.endswith("_ms")},
+        "build_roofline": build_roofline,
         "graph_bytes": graph.graph_bytes,
         "pops_per_query": round(cnt[0] / Q, 1), "dist_evals_per_query": round(cnt[1] / Q, 1),
         "rows_gathered_per_query": round(cnt[2] / Q, 1),

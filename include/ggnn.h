@@ -76,6 +76,9 @@ typedef struct {
  * stream (cf. the paper's construction-time split, Sec. 5.2.2). */
 typedef struct {
   float merge_ms, sym_ms, select_ms, stats_ms, total_ms;
+  /* work done by the searches of the build: iterations (adjacency rows read) and base rows
+   * gathered, for Merge and for the symmetric-linking queries */
+  uint64_t merge_pops, merge_rows, sym_pops, sym_rows;
 } ggnn_build_times;
 
 /* ---- construction (Alg. 3: BuildGraph; Alg. 6: RefineGraph) ------------------------ */

@@ -38,7 +38,8 @@ class GraphDesc(C.Structure):
 
 class BuildTimes(C.Structure):
     _fields_ = [("merge_ms", C.c_float), ("sym_ms", C.c_float), ("select_ms", C.c_float),
-                ("stats_ms", C.c_float), ("total_ms", C.c_float)]
+                ("stats_ms", C.c_float), ("total_ms", C.c_float), ("merge_pops", C.c_uint64),
+                ("merge_rows", C.c_uint64), ("sym_pops", C.c_uint64), ("sym_rows", C.c_uint64)]
 
 
 EXPORTS = [

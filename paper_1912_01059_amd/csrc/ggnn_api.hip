@@ -97,6 +97,7 @@ struct ggnn_graph {
   float* dnn1 = nullptr;        // N
   float* stats_dev = nullptr;   // 2
   double* stats_partial = nullptr;
+  unsigned long long* work_dev = nullptr;  // pops / rows gathered of merge and sym searches
   float stats[2] = {0.0f, 0.0f};
   const void* base = nullptr;   // borrowed
   float* norm = nullptr;        // cosine: owned unit-length copy
@@ -158,14 +159,15 @@ hipError_t launch_query(const GraphDev& G, int dtype, int metric, const void* qu
                            : launch_query_lds(G, dtype, metric, queries, Q, k, sp, every_layer, ids, dists, counters, stream);
 }
 hipError_t launch_merge(const GraphDev& G, int dtype, int metric, int l_top, int l_m, const SearchParams& sp,
-                        int32_t* out_rows, float* dnn1, hipStream_t stream) {
-  return use_registers(sp) ? launch_merge_reg(G, dtype, metric, l_top, l_m, sp, out_rows, dnn1, stream)
-                           : launch_merge_lds(G, dtype, metric, l_top, l_m, sp, out_rows, dnn1, stream);
+                        int32_t* out_rows, float* dnn1, unsigned long long* work, hipStream_t stream) {
+  return use_registers(sp) ? launch_merge_reg(G, dtype, metric, l_top, l_m, sp, out_rows, dnn1, work, stream)
+                           : launch_merge_lds(G, dtype, metric, l_top, l_m, sp, out_rows, dnn1, work, stream);
 }
 hipError_t launch_sym_search(const GraphDev& G, int dtype, int metric, int layer, int round, float w_mid,
-                             const SearchParams& sp, const SymBuffers& sb, hipStream_t stream) {
-  return use_registers(sp) ? launch_sym_search_reg(G, dtype, metric, layer, round, w_mid, sp, sb, stream)
-                           : launch_sym_search_lds(G, dtype, metric, layer, round, w_mid, sp, sb, stream);
+                             const SearchParams& sp, const SymBuffers& sb, unsigned long long* work,
+                             hipStream_t stream) {
+  return use_registers(sp) ? launch_sym_search_reg(G, dtype, metric, layer, round, w_mid, sp, sb, work, stream)
+                           : launch_sym_search_lds(G, dtype, metric, layer, round, w_mid, sp, sb, work, stream);
 }
 
 int ensure_sym_buffers(ggnn_graph* g) {
@@ -243,7 +245,7 @@ void ggnn_free(ggnn_graph* g) {
   for (int l = 0; l < kMaxLevels; l++) {
     hipFree(g->edges[l]); hipFree(g->to_lower[l]); hipFree(g->to_base[l]); hipFree(g->inv_count[l]);
   }
-  hipFree(g->edge_tmp); hipFree(g->dnn1); hipFree(g->stats_dev); hipFree(g->stats_partial); hipFree(g->norm);
+  hipFree(g->edge_tmp); hipFree(g->dnn1); hipFree(g->stats_dev); hipFree(g->stats_partial); hipFree(g->norm); hipFree(g->work_dev);
   release_sym_buffers(g);
   delete g;
 }
@@ -321,6 +323,8 @@ int ggnn_graph_create(const void* base_dev, int64_t N, int32_t D, int32_t K, int
   CREATE_TRY(launch_fill_i32((int32_t*)g->dnn1, N, 0, g->stream));
   CREATE_TRY(hipMalloc(&g->stats_dev, sizeof(float) * 2));
   CREATE_TRY(hipMalloc(&g->stats_partial, sizeof(double) * 2 * 1024));
+  CREATE_TRY(hipMalloc(&g->work_dev, sizeof(unsigned long long) * 8 * kWorkSlots));
+  CREATE_TRY(launch_fill_i32((int32_t*)g->work_dev, 16 * kWorkSlots, 0, g->stream));
   if (metric == GGNN_COSINE) {
     CREATE_TRY(hipMalloc(&g->norm, sizeof(float) * N * D));
     CREATE_TRY(launch_normalise(base_dev, dtype, N, D, g->norm, g->stream));
@@ -353,7 +357,7 @@ int ggnn_merge(ggnn_graph* g, int32_t l_top, int32_t l_m) {
   {
     PhaseTimer t(g->stream);
     GraphDev G = device_view(g);
-    HIP_TRY(launch_merge(G, row_dtype(g), g->metric, l_top, l_m, sp, g->edge_tmp, g->dnn1, g->stream));
+    HIP_TRY(launch_merge(G, row_dtype(g), g->metric, l_top, l_m, sp, g->edge_tmp, g->dnn1, g->work_dev, g->stream));
     // the buffer becomes the layer (inverse links of the layer are thereby discarded)
     HIP_TRY(hipMemcpyAsync(g->edges[l_m], g->edge_tmp, sizeof(int32_t) * g->n[l_m] * g->K, hipMemcpyDeviceToDevice, g->stream));
     HIP_TRY(launch_fill_i32(g->inv_count[l_m], g->n[l_m], 0, g->stream));
@@ -387,7 +391,7 @@ int ggnn_sym(ggnn_graph* g, int32_t layer) {
   HIP_TRY(launch_fill_i32(sb.nhold, n, 0, g->stream));
   HIP_TRY(launch_fill_i32(sb.head, n, -1, g->stream));
   for (int round = 0; round < knn; round++) {
-    HIP_TRY(launch_sym_search(G, row_dtype(g), g->metric, layer, round, g->w_mid, sp, sb, g->stream));
+    HIP_TRY(launch_sym_search(G, row_dtype(g), g->metric, layer, round, g->w_mid, sp, sb, g->work_dev, g->stream));
     bool first = true;
     for (;;) {
       HIP_TRY(launch_fill_i32(sb.pending, 1, 0, g->stream));
@@ -411,6 +415,7 @@ int ggnn_sym(ggnn_graph* g, int32_t layer) {
 int ggnn_build_steps(ggnn_graph* g) {
   if (!g) return fail(GGNN_ERR_INVALID, "graph is NULL");
   g->times = ggnn_build_times{};
+  HIP_TRY(launch_fill_i32((int32_t*)g->work_dev, 16 * kWorkSlots, 0, g->stream));
   PhaseTimer total(g->stream);
   int rc;
   for (int l_top = 0; l_top < g->L; l_top++) {
@@ -427,6 +432,12 @@ int ggnn_build_steps(ggnn_graph* g) {
     }
   }
   g->times.total_ms = total.stop();
+  std::vector<unsigned long long> w(8 * kWorkSlots);
+  HIP_TRY(hipMemcpy(w.data(), g->work_dev, sizeof(unsigned long long) * w.size(), hipMemcpyDeviceToHost));
+  for (int i = 0; i < kWorkSlots; i++) {
+    g->times.merge_pops += w[8 * i + 0]; g->times.merge_rows += w[8 * i + 1];
+    g->times.sym_pops += w[8 * i + 2]; g->times.sym_rows += w[8 * i + 3];
+  }
   return GGNN_OK;
 }
 

@@ -7,6 +7,9 @@
 
 namespace ggnn {
 
+// the work counters of the construction searches are spread over this many cache lines
+constexpr int kWorkSlots = 1024;
+
 // state of one symmetric-linking pass over a layer (device buffers owned by the graph)
 struct SymBuffers {
   int32_t* inv;       // n x ksym inverse links granted so far
@@ -29,9 +32,11 @@ struct SymBuffers {
                                   const SearchParams& sp, int every_layer, int32_t* ids, float* dists,             \
                                   uint32_t* counters, hipStream_t stream);                                         \
   hipError_t launch_merge##SUFFIX(const GraphDev& G, int dtype, int metric, int l_top, int l_m,                    \
-                                  const SearchParams& sp, int32_t* out_rows, float* dnn1, hipStream_t stream);     \
+                                  const SearchParams& sp, int32_t* out_rows, float* dnn1, unsigned long long* work, \
+                                  hipStream_t stream);                                                             \
   hipError_t launch_sym_search##SUFFIX(const GraphDev& G, int dtype, int metric, int layer, int round, float w_mid,\
-                                       const SearchParams& sp, const SymBuffers& sb, hipStream_t stream);
+                                       const SearchParams& sp, const SymBuffers& sb, unsigned long long* work,  \
+                                       hipStream_t stream);
 GGNN_SEARCH_LAUNCHERS(_reg)
 GGNN_SEARCH_LAUNCHERS(_lds)
 #undef GGNN_SEARCH_LAUNCHERS

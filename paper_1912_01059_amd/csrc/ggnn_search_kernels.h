@@ -81,7 +81,8 @@ __global__ __launch_bounds__(kWave) void query_kernel(GraphDev G, const uint8_t*
 
 template <class C, int DT, int NCH, int METRIC>
 __global__ __launch_bounds__(kWave) void merge_kernel(GraphDev G, int l_top, int l_m, SearchParams sp,
-                                                      int32_t* __restrict__ out_rows, float* __restrict__ dnn1) {
+                                                      int32_t* __restrict__ out_rows, float* __restrict__ dnn1,
+                                                      unsigned long long* __restrict__ work) {
   extern __shared__ __align__(16) unsigned char lds[];
   const int lane = lane_id();
   const int64_t z = blockIdx.x;
@@ -114,6 +115,11 @@ __global__ __launch_bounds__(kWave) void merge_kernel(GraphDev G, int l_top, int
   }
   c.store_row(G.K, out_rows + (size_t)z * G.K);
   if (l_m == 0 && lane == 0) dnn1[z] = (c.count() > 0) ? c.first_d() : 0.0f;
+  if (work && lane == 0) {  // totals for the roofline of the construction: pops, rows gathered
+    unsigned long long* w = work + (size_t)(blockIdx.x % kWorkSlots) * 8;  // one cache line per slot
+    atomicAdd(&w[0], (unsigned long long)c.n_pops());
+    atomicAdd(&w[1], (unsigned long long)c.n_gathers());
+  }
 }
 
 // Alg. 5 for neighbour number `round` of every point z: is there a path from x back to z
@@ -121,7 +127,8 @@ __global__ __launch_bounds__(kWave) void merge_kernel(GraphDev G, int l_top, int
 // best list of the search is kept as z's candidates for an inverse link.
 template <class C, int DT, int NCH, int METRIC>
 __global__ __launch_bounds__(kWave) void sym_search_kernel(GraphDev G, int layer, int round, float w_mid,
-                                                           SearchParams sp, SymBuffers sb) {
+                                                           SearchParams sp, SymBuffers sb,
+                                                           unsigned long long* __restrict__ work) {
   extern __shared__ __align__(16) unsigned char lds[];
   constexpr int E = Elem<DT>::per_chunk;
   const int lane = lane_id();
@@ -176,6 +183,11 @@ __global__ __launch_bounds__(kWave) void sym_search_kernel(GraphDev G, int layer
     c.template fetch<DT, NCH, METRIC, kPasses>(G, layer, p, q, -1);
   }
   if (!found && c.count() > 0) c.store_prefs(sb.pref + (size_t)z * sp.B, sb.npref + z);
+  if (work && lane == 0 && c.n_pops() > 0) {
+    unsigned long long* w = work + (size_t)(blockIdx.x % kWorkSlots) * 8;
+    atomicAdd(&w[2], (unsigned long long)c.n_pops());
+    atomicAdd(&w[3], (unsigned long long)c.n_gathers());
+  }
 }
 
 // ---- dispatch over element type, chunks per lane and metric ---------------------------
@@ -213,18 +225,19 @@ hipError_t launch_query_t(const GraphDev& G, int dtype, int metric, const void* 
 }
 template <class C>
 hipError_t launch_merge_t(const GraphDev& G, int dtype, int metric, int l_top, int l_m, const SearchParams& sp,
-                          int32_t* out_rows, float* dnn1, hipStream_t stream) {
+                          int32_t* out_rows, float* dnn1, unsigned long long* work, hipStream_t stream) {
   const dim3 grid((unsigned)G.n[l_m]);
   const size_t lds = C::lds_bytes(sp);
-  GGNN_DISPATCH(C, merge_kernel, G, l_top, l_m, sp, out_rows, dnn1);
+  GGNN_DISPATCH(C, merge_kernel, G, l_top, l_m, sp, out_rows, dnn1, work);
   return hipGetLastError();
 }
 template <class C>
 hipError_t launch_sym_search_t(const GraphDev& G, int dtype, int metric, int layer, int round, float w_mid,
-                               const SearchParams& sp, const SymBuffers& sb, hipStream_t stream) {
+                               const SearchParams& sp, const SymBuffers& sb, unsigned long long* work,
+                               hipStream_t stream) {
   const dim3 grid((unsigned)G.n[layer]);
   const size_t lds = C::lds_bytes(sp);
-  GGNN_DISPATCH(C, sym_search_kernel, G, layer, round, w_mid, sp, sb);
+  GGNN_DISPATCH(C, sym_search_kernel, G, layer, round, w_mid, sp, sb, work);
   return hipGetLastError();
 }
 

@@ -8,12 +8,13 @@ hipError_t launch_query_reg(const GraphDev& G, int dtype, int metric, const void
   return launch_query_t<RegCache>(G, dtype, metric, queries, Q, k, sp, every_layer, ids, dists, counters, stream);
 }
 hipError_t launch_merge_reg(const GraphDev& G, int dtype, int metric, int l_top, int l_m, const SearchParams& sp,
-                            int32_t* out_rows, float* dnn1, hipStream_t stream) {
-  return launch_merge_t<RegCache>(G, dtype, metric, l_top, l_m, sp, out_rows, dnn1, stream);
+                            int32_t* out_rows, float* dnn1, unsigned long long* work, hipStream_t stream) {
+  return launch_merge_t<RegCache>(G, dtype, metric, l_top, l_m, sp, out_rows, dnn1, work, stream);
 }
 hipError_t launch_sym_search_reg(const GraphDev& G, int dtype, int metric, int layer, int round, float w_mid,
-                                 const SearchParams& sp, const SymBuffers& sb, hipStream_t stream) {
-  return launch_sym_search_t<RegCache>(G, dtype, metric, layer, round, w_mid, sp, sb, stream);
+                                 const SearchParams& sp, const SymBuffers& sb, unsigned long long* work,
+                                 hipStream_t stream) {
+  return launch_sym_search_t<RegCache>(G, dtype, metric, layer, round, w_mid, sp, sb, work, stream);
 }
 #ifdef GGNN_PHASE_TIMING
 hipError_t read_phase_cycles(unsigned long long* out16, int reset) {

@@ -105,7 +105,7 @@ def main():
     if a.report == "quality":
         g, secs = build()
         out = {"report": "quality", "workload": a.workload, "levels": a.levels, "build_seconds": round(secs, 3),
-               "phases_ms": {kk: round(v, 2) for kk, v in g.times().items()}}
+               "phases_ms": {kk: round(v, 2) for kk, v in g.times().items() if kk.endswith("_ms")}}
         t = g.times()
         tot = t["merge_ms"] + t["sym_ms"] + t["select_ms"] + t["stats_ms"]
         out["split_percent"] = {kk[:-3]: round(100.0 * t[kk] / tot, 2) for kk in ("merge_ms", "sym_ms", "select_ms", "stats_ms")}
@@ -124,17 +124,16 @@ def main():
             g, secs = build(sym_constraint=on)
             print(json.dumps(dict(report="sym", constraint=on, build_seconds=round(secs, 3),
                                   inverse_links_per_row=round(float(g.export_inv_count(0).mean()), 3),
-                                  phases_ms={kk: round(v, 2) for kk, v in g.times().items()}, **query_line(g))))
+                                  phases_ms={kk: round(v, 2) for kk, v in g.times().items() if kk.endswith("_ms")}, **query_line(g))))
             del g
     elif a.report == "tau_b":
         for tb in (0.1, 0.2, 0.3, 0.5, 0.8):
-            g, secs = build(tau_build=tb, refinements=-1 if False else 2)
+            g, secs = build(tau_build=tb)
             print(json.dumps(dict(report="tau_b", tau_build=tb, build_seconds=round(secs, 3),
                                   graph=graph_quality(torch, g, base, cosine, max(1, base.shape[0] // 2000)), **query_line(g))))
             del g
     elif a.report == "batch":
         g, secs = build()
-        import numpy as np
         reps = -(-200_000 // q.shape[0])
         big = q.repeat(reps, 1)[torch.randperm(q.shape[0] * reps, device=dev)].contiguous()
         for n in (100, 300, 1000, 3000, 10_000, 30_000, 100_000, 200_000):
