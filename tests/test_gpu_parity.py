@@ -262,3 +262,50 @@ def test_build_quality_and_recall(ggnn, R, sift10k, sift10k_gt):
     assert g.export_inv_count(0).max() <= K - K // 2
     ids, _ = g.query(dev(queries), 10, 10, 0.3, every_layer=True)
     assert R.recall(ids.cpu().numpy(), sift10k_gt[0]) >= 0.99
+
+
+# ------------------------------------------------------------------------------ construction, varied shapes
+
+@pytest.mark.parametrize("case", [
+    dict(N=200, D=16, K=12, L=2, s=32, kind="real"),            # tiny, one bottom segment per 32 points
+    dict(N=777, D=8, K=6, L=3, s=16, kind="int"),               # ragged segments, small s
+    dict(N=2000, D=32, K=40, L=3, s=32, kind="int"),            # K above the segment size: rows padded with -1 at first
+    dict(N=1500, D=100, K=24, L=2, s=32, kind="cosine"),        # cosine, D not a multiple of 32
+    dict(N=3000, D=128, K=24, L=3, s=32, kind="u8"),            # uint8 rows
+    dict(N=1200, D=96, K=25, L=3, s=32, kind="real"),           # odd K: k_nn = 12, k_sym = 13
+    dict(N=890, D=64, K=24, L=2, s=64, kind="dups"),            # duplicated rows: distance ties, zero distances
+])
+def test_full_build_matches_oracle_on_varied_shapes(ggnn, R, case):
+    rng = np.random.default_rng(case["N"])
+    N, D = case["N"], case["D"]
+    metric_o, metric_g = R.L2, ggnn.L2
+    if case["kind"] in ("real", "cosine"):
+        base = rng.standard_normal((N, D)).astype(np.float32)
+        if case["kind"] == "cosine":
+            base *= np.exp(rng.normal(0, 0.5, (N, 1))).astype(np.float32)
+            metric_o, metric_g = R.COSINE, ggnn.COSINE
+    elif case["kind"] == "u8":
+        base = rng.integers(0, 256, (N, D)).astype(np.uint8)
+    else:
+        base = rng.integers(0, 256, (N, D)).astype(np.float32)
+        if case["kind"] == "dups":
+            base[N // 2:] = base[: N - N // 2]
+    p = R.default_params(refinements=1, visited_cap=96, max_iter=96)
+    og = R.Graph(base, case["K"], case["L"], s=case["s"], metric=metric_o, seed=5).build(p)
+    g = ggnn.build(dev(base), case["K"], case["L"], seed=5, metric=metric_g, segment_size=case["s"], refinements=1,
+                   visited_cap=96, max_iter=96)
+    assert g.n == og.n
+    for l in range(g.L):
+        e, tl, tb = g.export_layer(l)
+        assert np.array_equal(e, og.edges(l)), "layer %d" % l
+        if l >= 1:
+            assert np.array_equal(tl, og.to_lower(l)) and np.array_equal(tb, og.to_base(l))
+        assert np.array_equal(g.export_inv_count(l), og.inv_count(l))
+    d, mean, mx = g.export_dnn()
+    assert np.array_equal(d.view(np.uint32), og.dnn1().view(np.uint32)) and mx == og.stats()[1]
+    # queries on it, both descent modes, results padded when fewer than k points are reachable
+    q = base[rng.integers(0, N, 50)].copy()
+    for every in (False, True):
+        ids, dd = g.query(dev(q), 10, 10, 0.3, every_layer=every)
+        rids, rd = og.query(q, 10, 10, 0.3, every_layer=every)
+        assert_same_results(ids, dd, rids, rd)
