@@ -139,6 +139,17 @@ int ggnn_query_ex(const ggnn_graph* g, const void* queries_dev, int64_t Q, int32
                   int32_t pq_cap, int32_t visited_cap, int32_t max_iter, int32_t every_layer, void* stream,
                   int32_t* ids_dev, float* dists_dev, uint32_t* counters_dev, int32_t asynchronous);
 
+/* ---- sharding on one GPU (Sec. 4.5) -------------------------------------------------- */
+
+/* Merges the answers S independent shards gave to the same Q queries.  ids_dev / dists_dev:
+ * S x Q x k (shard-major), each list ascending and padded with id -1 as ggnn_query writes it;
+ * offsets_dev: S int32, the global id of the first base row of each shard.  out_*_dev: Q x k, the
+ * k best overall ascending by (distance, global id), padded with -1 / +inf.  S * k * 8 bytes must
+ * fit one workgroup's LDS.  stream: hipStream_t; asynchronous != 0 returns after the launch. */
+int ggnn_merge_shards(int32_t S, int64_t Q, int32_t k, const int32_t* ids_dev, const float* dists_dev,
+                      const int32_t* offsets_dev, int32_t* out_ids_dev, float* out_dists_dev, void* stream,
+                      int32_t asynchronous);
+
 /* ---- graph access ------------------------------------------------------------------- */
 
 int ggnn_graph_info(const ggnn_graph* g, ggnn_graph_desc* out);

@@ -829,3 +829,31 @@ int ggnn_ref_build(ggnn_ref_graph* g, const ggnn_ref_build_params* p) {
   }
   return 0;
 }
+
+/* ------------------------------------------------------------------- shards */
+
+/* Sec. 4.5: merge of the per-shard answers (plain definition: pool all, sort, take k). */
+int ggnn_ref_merge_shards(int S, int64_t Q, int k, const int32_t* ids, const float* dists,
+                          const int32_t* offsets, int32_t* out_ids, float* out_dists) {
+  if (S < 1 || k < 1 || Q < 0) return -1;
+  for (int64_t q = 0; q < Q; q++) {
+    ent* top = (ent*)malloc(sizeof(ent) * (size_t)k);
+    int cnt = 0;
+    for (int s = 0; s < S; s++) {
+      for (int j = 0; j < k; j++) {
+        int32_t id = ids[((int64_t)s * Q + q) * k + j];
+        if (id < 0) continue;
+        ent e;
+        e.id = id + offsets[s];
+        e.d = dists[((int64_t)s * Q + q) * k + j];
+        sorted_insert(top, &cnt, k, e);
+      }
+    }
+    for (int j = 0; j < k; j++) {
+      out_ids[q * k + j] = (j < cnt) ? top[j].id : -1;
+      out_dists[q * k + j] = (j < cnt) ? top[j].d : INFINITY;
+    }
+    free(top);
+  }
+  return 0;
+}

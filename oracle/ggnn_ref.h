@@ -91,6 +91,12 @@ int ggnn_ref_query(const ggnn_ref_graph* g, const void* queries, int64_t Q, int 
                    int B, float tau, int P, int V, int max_iter, int every_layer,
                    int32_t* ids, float* dists, uint32_t* counters);
 
+/* Sec. 4.5 (sharding): every query is answered on every shard; the S per-shard lists (each Q*k,
+ * ascending, padded with id -1) are merged into the k best overall by (distance, global id),
+ * global id = offset of the shard + id within the shard.  ids / dists are S*Q*k. */
+int ggnn_ref_merge_shards(int S, int64_t Q, int k, const int32_t* ids, const float* dists,
+                          const int32_t* offsets, int32_t* out_ids, float* out_dists);
+
 int ggnn_ref_num_threads(void);
 
 #ifdef __cplusplus

@@ -63,6 +63,7 @@ def lib():
         L.ggnn_ref_build.argtypes = [vp, C.POINTER(BuildParams)]
         L.ggnn_ref_query.argtypes = [vp, vp, i64, C.c_int, C.c_int, f32, C.c_int, C.c_int, C.c_int, C.c_int, vp, vp, vp]
         L.ggnn_ref_num_threads.restype = C.c_int
+        L.ggnn_ref_merge_shards.argtypes = [C.c_int, i64, C.c_int, vp, vp, vp, vp, vp]
         _lib = L
     return _lib
 
@@ -204,6 +205,19 @@ class Graph:
         if rc != 0:
             raise RuntimeError("query failed: %d" % rc)
         return (ids, dists, cnt) if counters else (ids, dists)
+
+
+def merge_shards(ids, dists, offsets):
+    """ids, dists: S x Q x k per-shard answers; offsets: S shard offsets.  Returns the merged Q x k."""
+    ids = np.ascontiguousarray(ids, np.int32)
+    dists = np.ascontiguousarray(dists, np.float32)
+    offsets = np.ascontiguousarray(offsets, np.int32)
+    S, Q, k = ids.shape
+    out_i = np.empty((Q, k), np.int32)
+    out_d = np.empty((Q, k), np.float32)
+    rc = lib().ggnn_ref_merge_shards(S, Q, k, _ptr(ids), _ptr(dists), _ptr(offsets), _ptr(out_i), _ptr(out_d))
+    assert rc == 0, rc
+    return out_i, out_d
 
 
 def recall(ids, gt):

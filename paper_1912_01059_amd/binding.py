@@ -46,7 +46,7 @@ EXPORTS = [
     "ggnn_build", "ggnn_build_ex", "ggnn_graph_create", "ggnn_select", "ggnn_merge", "ggnn_sym",
     "ggnn_build_steps", "ggnn_build_get_times", "ggnn_query", "ggnn_query_ex", "ggnn_graph_info",
     "ggnn_graph_export", "ggnn_graph_import", "ggnn_graph_export_dnn", "ggnn_graph_import_dnn",
-    "ggnn_graph_export_inv_count", "ggnn_set_cache_mode", "ggnn_gather_probe", "ggnn_free", "ggnn_last_error",
+    "ggnn_graph_export_inv_count", "ggnn_set_cache_mode", "ggnn_gather_probe", "ggnn_merge_shards", "ggnn_free", "ggnn_last_error",
 ]
 
 
@@ -77,6 +77,7 @@ def lib():
         L.ggnn_graph_export_inv_count.argtypes = [vp, i32, vp]
         L.ggnn_set_cache_mode.argtypes = [i32]
         L.ggnn_gather_probe.argtypes = [vp, i64, i32, vp, i64, i32, vp, vp]
+        L.ggnn_merge_shards.argtypes = [i32, i64, i32, vp, vp, vp, vp, vp, vp, i32]
         L.ggnn_free.argtypes = [vp]
         L.ggnn_free.restype = None
         L.ggnn_last_error.restype = C.c_char_p
@@ -99,6 +100,40 @@ def gather_probe(rows, ids, rows_per_wave, out=None):
     _check(lib().ggnn_gather_probe(_dev_ptr(rows), rows.shape[0], rows.shape[1] * rows.element_size(), _dev_ptr(ids), n,
                                    rows_per_wave, _dev_ptr(out), C.c_void_p(torch.cuda.current_stream().cuda_stream)))
     return out
+
+
+def merge_shards(ids, dists, offsets):
+    """ggnn_merge_shards: ids / dists are S x Q x k GPU tensors, offsets an S int32 GPU tensor."""
+    import torch
+    S, Q, k = ids.shape
+    out_i = torch.empty((Q, k), dtype=torch.int32, device=ids.device)
+    out_d = torch.empty((Q, k), dtype=torch.float32, device=ids.device)
+    _check(lib().ggnn_merge_shards(S, Q, k, _dev_ptr(ids), _dev_ptr(dists), _dev_ptr(offsets), _dev_ptr(out_i), _dev_ptr(out_d),
+                                   C.c_void_p(torch.cuda.current_stream().cuda_stream), 0))
+    return out_i, out_d
+
+
+class ShardedIndex:
+    """Sec. 4.5 on one GPU: the base set is cut into S contiguous shards, each with its own graph;
+    a query batch is answered on every shard and the answers are merged on the GPU."""
+
+    def __init__(self, base, shards, K, levels, **build_args):
+        import torch
+        N = base.shape[0]
+        bounds = [N * i // shards for i in range(shards + 1)]
+        self.parts = [base[bounds[i]:bounds[i + 1]].contiguous() for i in range(shards)]
+        self.offsets = torch.tensor(bounds[:-1], dtype=torch.int32, device=base.device)
+        self.graphs = [build(p, K, levels, **build_args) for p in self.parts]
+
+    def query(self, queries, k, beam, slack, **query_args):
+        import torch
+        Q = queries.shape[0]
+        S = len(self.graphs)
+        ids = torch.empty((S, Q, k), dtype=torch.int32, device=queries.device)
+        dists = torch.empty((S, Q, k), dtype=torch.float32, device=queries.device)
+        for s, g in enumerate(self.graphs):
+            g.query(queries, k, beam, slack, out=(ids[s], dists[s]), **query_args)
+        return merge_shards(ids, dists, self.offsets)
 
 
 def last_error() -> str:

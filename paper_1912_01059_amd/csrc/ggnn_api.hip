@@ -225,6 +225,19 @@ extern "C" {
 
 const char* ggnn_last_error(void) { return g_err; }
 
+int ggnn_merge_shards(int32_t S, int64_t Q, int32_t k, const int32_t* ids_dev, const float* dists_dev,
+                      const int32_t* offsets_dev, int32_t* out_ids_dev, float* out_dists_dev, void* stream,
+                      int32_t asynchronous) {
+  if (S < 1 || k < 1 || Q < 0) return fail(GGNN_ERR_INVALID, "S, k must be positive and Q not negative");
+  if (Q > 0x7FFFFFFFll) return fail(GGNN_ERR_INVALID, "Q too large");
+  if (Q == 0) return GGNN_OK;
+  if (!ids_dev || !dists_dev || !offsets_dev || !out_ids_dev || !out_dists_dev) return fail(GGNN_ERR_INVALID, "NULL device pointer");
+  if ((size_t)S * k * 8 > kMaxLds) return fail(GGNN_ERR_LIMIT, "S * k = %lld keys do not fit one workgroup's LDS", (long long)S * k);
+  HIP_TRY(launch_merge_shards(S, Q, k, ids_dev, dists_dev, offsets_dev, out_ids_dev, out_dists_dev, (hipStream_t)stream));
+  if (!asynchronous) HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
+  return GGNN_OK;
+}
+
 int ggnn_gather_probe(const void* rows_dev, int64_t n_rows, int32_t row_bytes, const int32_t* ids_dev, int64_t n_ids,
                       int32_t rows_per_wave, uint32_t* out_dev, void* stream) {
   if (!rows_dev || !ids_dev || !out_dev) return fail(GGNN_ERR_INVALID, "NULL device pointer");

@@ -326,6 +326,47 @@ hipError_t launch_gather_probe(const void* rows, int row_bytes, const int32_t* i
   return hipGetLastError();
 }
 
+// Sec. 4.5 (sharding): the S per-shard answers of one query (each k entries, ascending, padded
+// with id -1) are merged into the k best overall by (distance, global id).  One wavefront per
+// query: the S*k keys go to LDS, every valid key counts the smaller ones, and a key of rank r < k
+// is result r (the keys are distinct because global ids are).
+__global__ __launch_bounds__(kWave) void merge_shards_kernel(int S, int64_t Q, int k, const int32_t* __restrict__ ids,
+                                                             const float* __restrict__ dists,
+                                                             const int32_t* __restrict__ offsets,
+                                                             int32_t* __restrict__ out_ids, float* __restrict__ out_dists) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  u64* keys = (u64*)lds;
+  const int lane = threadIdx.x;
+  const int64_t q = blockIdx.x;
+  const int n = S * k;
+  for (int i = lane; i < n; i += kWave) {
+    const int s = i / k, j = i - s * k;
+    const int32_t id = ids[((size_t)s * Q + q) * k + j];
+    keys[i] = (id < 0) ? ~0ull : make_key(dists[((size_t)s * Q + q) * k + j], id + offsets[s]);
+  }
+  for (int j = lane; j < k; j += kWave) {
+    out_ids[(size_t)q * k + j] = -1;
+    out_dists[(size_t)q * k + j] = INFINITY;
+  }
+  __syncthreads();
+  for (int i = lane; i < n; i += kWave) {
+    const u64 key = keys[i];
+    if (key == ~0ull) continue;
+    int r = 0;
+    for (int j = 0; j < n; j++) r += keys[j] < key;
+    if (r < k) {
+      out_ids[(size_t)q * k + r] = key_id(key);
+      out_dists[(size_t)q * k + r] = key_d(key);
+    }
+  }
+}
+hipError_t launch_merge_shards(int S, int64_t Q, int k, const int32_t* ids, const float* dists, const int32_t* offsets,
+                               int32_t* out_ids, float* out_dists, hipStream_t stream) {
+  if (Q <= 0) return hipSuccess;
+  merge_shards_kernel<<<(unsigned)Q, kWave, (size_t)S * k * 8, stream>>>(S, Q, k, ids, dists, offsets, out_ids, out_dists);
+  return hipGetLastError();
+}
+
 static inline unsigned blocks_for(int64_t n) { return (unsigned)((n + 255) / 256); }
 
 hipError_t launch_sym_propose(const GraphDev& G, int layer, const SymBuffers& sb, int B, hipStream_t stream);

@@ -44,6 +44,8 @@ GGNN_SEARCH_LAUNCHERS(_lds)
 // construction kernels (ggnn_build.hip)
 hipError_t launch_gather_probe(const void* rows, int row_bytes, const int32_t* ids, int64_t n, int rows_per_wave,
                                uint32_t* out, hipStream_t stream);
+hipError_t launch_merge_shards(int S, int64_t Q, int k, const int32_t* ids, const float* dists, const int32_t* offsets,
+                               int32_t* out_ids, float* out_dists, hipStream_t stream);
 hipError_t launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t stream);
 hipError_t launch_normalise(const void* base, int dtype, int64_t N, int D, float* out, hipStream_t stream);
 hipError_t launch_select(const GraphDev& G, int l_top, const float* dnn1, int32_t* to_lower, int32_t* to_base,

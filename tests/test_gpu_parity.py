@@ -309,3 +309,34 @@ def test_full_build_matches_oracle_on_varied_shapes(ggnn, R, case):
         ids, dd = g.query(dev(q), 10, 10, 0.3, every_layer=every)
         rids, rd = og.query(q, 10, 10, 0.3, every_layer=every)
         assert_same_results(ids, dd, rids, rd)
+
+
+# ------------------------------------------------------------------------------ shards
+
+def test_shard_merge_matches_oracle(ggnn, R):
+    rng = np.random.default_rng(8)
+    for S, Q, k in [(1, 5, 3), (4, 130, 10), (7, 64, 100), (16, 33, 1)]:
+        d = np.sort(rng.integers(0, 50, (S, Q, k)).astype(np.float32), axis=2)     # many ties across shards
+        ids = np.stack([np.stack([rng.choice(1000, k, replace=False) for _ in range(Q)]) for _ in range(S)]).astype(np.int32)
+        pad = rng.random((S, Q)) < 0.3
+        for s in range(S):
+            for q in range(Q):
+                if pad[s, q]:
+                    cut = int(rng.integers(0, k + 1))
+                    ids[s, q, cut:] = -1
+                    d[s, q, cut:] = np.inf
+        offsets = (np.arange(S) * 1000).astype(np.int32)
+        gi, gd = ggnn.merge_shards(dev(ids), dev(d), dev(offsets))
+        ri, rd = R.merge_shards(ids, d, offsets)
+        assert np.array_equal(gi.cpu().numpy(), ri) and np.array_equal(gd.cpu().numpy().view(np.uint32), rd.view(np.uint32))
+
+
+def test_sharded_index_recall(ggnn, R, sift10k, sift10k_gt):
+    """Four shards of config 1, each with its own graph: merged answers against exhaustive search."""
+    base, queries, cfg = sift10k
+    idx = ggnn.ShardedIndex(dev(base), 4, cfg["K"], 3, seed=3)
+    ids, d = idx.query(dev(queries), 10, 10, 0.3, every_layer=True)
+    assert R.recall(ids.cpu().numpy(), sift10k_gt[0]) >= 0.99
+    got = ids.cpu().numpy()
+    d2 = ((base[got[0]].astype(np.int64) - queries[0].astype(np.int64)) ** 2).sum(1)
+    assert np.array_equal(d.cpu().numpy()[0], np.sqrt(d2.astype(np.float32)))

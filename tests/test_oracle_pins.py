@@ -518,3 +518,26 @@ def test_recall_is_stable_across_seeds():
         g = R.Graph(base, 24, 3, seed=seed).build()
         rec.append(R.recall(g.query(queries, 10, 10, 0.3, every_layer=True)[0], gt))
     assert min(rec) >= 0.98 and max(rec) - min(rec) <= 0.02
+
+
+# ---------------------------------------------------------------- shards
+
+def test_shard_merge_equals_search_over_the_whole_set():
+    """Sec. 4.5: exhaustive answers of the shards, merged, are the exhaustive answer of the whole set."""
+    rng = np.random.default_rng(21)
+    base = rng.integers(0, 256, (900, 16)).astype(np.float32)
+    q = rng.integers(0, 256, (40, 16)).astype(np.float32)
+    bounds = [0, 250, 610, 900]
+    ids, dists = [], []
+    for lo, hi in zip(bounds[:-1], bounds[1:]):
+        i, d = R.bruteforce(base[lo:hi], q, 7)
+        ids.append(i)
+        dists.append(d)
+    mi, md = R.merge_shards(np.stack(ids), np.stack(dists), bounds[:-1])
+    gi, gd = R.bruteforce(base, q, 7)
+    assert np.array_equal(mi, gi) and np.array_equal(md, gd)
+    # padded lists: a shard with fewer than k points
+    ids[0][:, 3:] = -1
+    dists[0][:, 3:] = np.inf
+    mi2, md2 = R.merge_shards(np.stack(ids), np.stack(dists), bounds[:-1])
+    assert (mi2 >= 0).all() and (np.diff(md2, axis=1) >= 0).all()
