@@ -170,8 +170,9 @@ int ggnn_graph_import_dnn(ggnn_graph* g, const float* dnn1_host, float mean, flo
 /* number of inverse links each row of `layer` holds after the last ggnn_sym (host, n[layer]) */
 int ggnn_graph_export_inv_count(const ggnn_graph* g, int32_t layer, int32_t* count_host);
 
-/* Where best and prioq live during a search: 0 (default) in registers whenever both hold at most
- * 64 entries, otherwise in LDS; 1 always in LDS.  Results do not depend on it.  Process-wide. */
+/* Where best and prioq live during a search: 0 (default) in registers whenever prioq holds at most
+ * 64 entries and best at most 64 (128 for user queries), otherwise in LDS; 1 always in LDS.
+ * Results do not depend on it.  Process-wide. */
 int ggnn_set_cache_mode(int32_t mode);
 
 /* Measurement aid (not part of the method): gathers rows ids_dev[0..n_ids) (each in [0, n_rows), not

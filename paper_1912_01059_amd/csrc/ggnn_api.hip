@@ -136,16 +136,22 @@ GraphDev device_view(const ggnn_graph* g) {
 }
 int row_dtype(const ggnn_graph* g) { return g->norm ? GGNN_F32 : g->dtype; }
 
-bool use_registers(const SearchParams& sp) { return g_cache_mode == 0 && sp.B <= kWave && sp.P <= kWave; }
+// where the lists of a search live: 1 / 2 = registers with best in one / two registers per lane, 0 = LDS
+int register_slots(const SearchParams& sp, bool user_query) {
+  if (g_cache_mode != 0 || sp.P > kWave) return 0;
+  if (sp.B <= kWave) return 1;
+  return (user_query && sp.B <= 2 * kWave) ? 2 : 0;
+}
 
-int make_search_params(int B, int P, int V, int max_iter, float tau, float dnn, SearchParams* sp) {
+int make_search_params(int B, int P, int V, int max_iter, float tau, float dnn, SearchParams* sp, bool user_query = false) {
   if (B < 1 || P < 1 || V < 1 || max_iter < 0) return fail(GGNN_ERR_INVALID, "cache capacities must be positive");
   if (max_iter > V) return fail(GGNN_ERR_INVALID, "max_iter (%d) must not exceed visited_cap (%d)", max_iter, V);
   sp->B = B; sp->P = P; sp->max_iter = max_iter;
   sp->H = next_pow2(2 * (max_iter > 0 ? max_iter : 1));
   if (sp->H < 64) sp->H = 64;
   sp->tau = tau; sp->dnn = dnn;
-  const size_t need = use_registers(*sp) ? RegCache::lds_bytes(*sp) : LdsCache::lds_bytes(*sp);
+  const int slots = register_slots(*sp, user_query);
+  const size_t need = slots == 1 ? RegCache::lds_bytes(*sp) : slots == 2 ? RegCache2::lds_bytes(*sp) : LdsCache::lds_bytes(*sp);
   if (need > kMaxLds)
     return fail(GGNN_ERR_LIMIT, "cache of best=%d prioq=%d visited=%d needs %zu bytes of LDS, limit %zu", B, P, V,
                 need, kMaxLds);
@@ -155,18 +161,20 @@ int make_search_params(int B, int P, int V, int max_iter, float tau, float dnn, 
 hipError_t launch_query(const GraphDev& G, int dtype, int metric, const void* queries, int64_t Q, int k,
                         const SearchParams& sp, int every_layer, int32_t* ids, float* dists, uint32_t* counters,
                         hipStream_t stream) {
-  return use_registers(sp) ? launch_query_reg(G, dtype, metric, queries, Q, k, sp, every_layer, ids, dists, counters, stream)
-                           : launch_query_lds(G, dtype, metric, queries, Q, k, sp, every_layer, ids, dists, counters, stream);
+  const int slots = register_slots(sp, true);
+  if (slots == 1) return launch_query_reg(G, dtype, metric, queries, Q, k, sp, every_layer, ids, dists, counters, stream);
+  if (slots == 2) return launch_query_reg2(G, dtype, metric, queries, Q, k, sp, every_layer, ids, dists, counters, stream);
+  return launch_query_lds(G, dtype, metric, queries, Q, k, sp, every_layer, ids, dists, counters, stream);
 }
 hipError_t launch_merge(const GraphDev& G, int dtype, int metric, int l_top, int l_m, const SearchParams& sp,
                         int32_t* out_rows, float* dnn1, unsigned long long* work, hipStream_t stream) {
-  return use_registers(sp) ? launch_merge_reg(G, dtype, metric, l_top, l_m, sp, out_rows, dnn1, work, stream)
+  return register_slots(sp, false) == 1 ? launch_merge_reg(G, dtype, metric, l_top, l_m, sp, out_rows, dnn1, work, stream)
                            : launch_merge_lds(G, dtype, metric, l_top, l_m, sp, out_rows, dnn1, work, stream);
 }
 hipError_t launch_sym_search(const GraphDev& G, int dtype, int metric, int layer, int round, float w_mid,
                              const SearchParams& sp, const SymBuffers& sb, unsigned long long* work,
                              hipStream_t stream) {
-  return use_registers(sp) ? launch_sym_search_reg(G, dtype, metric, layer, round, w_mid, sp, sb, work, stream)
+  return register_slots(sp, false) == 1 ? launch_sym_search_reg(G, dtype, metric, layer, round, w_mid, sp, sb, work, stream)
                            : launch_sym_search_lds(G, dtype, metric, layer, round, w_mid, sp, sb, work, stream);
 }
 
@@ -496,7 +504,7 @@ int ggnn_query_ex(const ggnn_graph* g, const void* queries_dev, int64_t Q, int32
   const int it = max_iter > 0 ? max_iter : V;
   SearchParams sp;
   // user queries bound the slack by the maximum first-neighbour distance (Eq. 2, Eq. 3)
-  int rc = make_search_params(B, P, V, it, slack, g->stats[1], &sp);
+  int rc = make_search_params(B, P, V, it, slack, g->stats[1], &sp, true);
   if (rc != GGNN_OK) return rc;
   hipStream_t st = stream ? (hipStream_t)stream : g->stream;
   GraphDev G = device_view(g);

@@ -38,6 +38,9 @@ struct SymBuffers {
                                        const SearchParams& sp, const SymBuffers& sb, unsigned long long* work,  \
                                        hipStream_t stream);
 GGNN_SEARCH_LAUNCHERS(_reg)
+hipError_t launch_query_reg2(const GraphDev& G, int dtype, int metric, const void* queries, int64_t Q, int k,
+                             const SearchParams& sp, int every_layer, int32_t* ids, float* dists, uint32_t* counters,
+                             hipStream_t stream);
 GGNN_SEARCH_LAUNCHERS(_lds)
 #undef GGNN_SEARCH_LAUNCHERS
 

@@ -1,5 +1,6 @@
-// The cache of Sec. 3.1.1 for best and prioq of at most 64 entries each: both lists live in
-// registers, entry i in lane i (packed (distance, id) keys, empty = all ones), so that a sorted
+// The cache of Sec. 3.1.1 for a prioq of at most 64 and a best list of at most 64 * NB entries:
+// both lists live in registers, entry i in lane i mod 64 of register i / 64 (packed (distance, id)
+// keys, empty = all ones), so that a sorted
 // insertion is one compare, one whole-wave shift (DPP) and a select, and a pop is a shift the
 // other way.  visited is an exact hash set in LDS; the same table also remembers points that
 // were evaluated and rejected: the threshold of Eq. 2 never grows during a search on one layer,
@@ -48,8 +49,10 @@ __device__ unsigned long long g_phase_cycles[16];
 #define GGNN_TICK(i)
 #endif
 
-struct RegCache {
+template <int NB>
+struct RegCacheT {
   static constexpr bool kInRegisters = true;
+  static constexpr int kBestSlots = NB;
 #ifdef GGNN_PHASE_TIMING
   uint32_t ph[12] = {0};
   __device__ void flush_phases() {
@@ -57,7 +60,7 @@ struct RegCache {
       for (int i = 0; i < 12; i++) atomicAdd(&g_phase_cycles[i], (unsigned long long)ph[i]);
   }
 #endif
-  u64 best, pq;                 // lane i: entry i, kEmptyKey beyond the fill level / capacity
+  u64 best[NB], pq;             // entry i: best[i / 64] of lane i % 64; kEmptyKey beyond the fill level
   int32_t B, P, nb, np;
   int32_t iter, max_iter;
   float tau, dnn, radius, d1, dk, thr_now;
@@ -77,11 +80,12 @@ struct RegCache {
     while (h < 2 * max_iter + 256) h <<= 1;
     return h;
   }
-  // the staging area of Transform (4 x 64 keys) shares its memory with the hash table, which
-  // Transform empties anyway
+  // the staging area of Transform ((2 NB + 2) x 64 keys) shares its memory with the hash table,
+  // which Transform empties anyway
   __host__ __device__ static size_t hash_bytes(const SearchParams& sp) {
     const size_t h = (size_t)hash_slots(sp.max_iter) * 4;
-    return h > 4 * 64 * 8 ? h : 4 * 64 * 8;
+    const size_t st = (size_t)(2 * NB + 2) * 64 * 8;
+    return h > st ? h : st;
   }
   __host__ __device__ static size_t lds_bytes(const SearchParams& sp) {
     return hash_bytes(sp) + 3 * 64 * 4 + kListedBuckets / 8;
@@ -129,7 +133,9 @@ struct RegCache {
   }
   // Alg. 2 Init
   __device__ void init() {
-    best = pq = kEmptyKey;
+#pragma unroll
+    for (int e = 0; e < NB; e++) best[e] = kEmptyKey;
+    pq = kEmptyKey;
     nb = np = 0; iter = 0; pops = evals = gathers = 0;
     radius = INFINITY; d1 = dk = thr_now = INFINITY; last_best = kEmptyKey;
     listed_clear();
@@ -174,8 +180,10 @@ struct RegCache {
   // Eq. 2; d1 / dk are best[0].d and best[B-1].d (+inf while best is not full)
   __device__ float thr() const { return thr_now; }
   __device__ void refresh_bounds() {
-    d1 = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(best >> 32), 0));
-    last_best = read_lane_u64(best, B - 1);  // all ones while best is not full
+    d1 = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(best[0] >> 32), 0));
+#pragma unroll
+    for (int e = 0; e < NB; e++)
+      if (((B - 1) >> 6) == e) last_best = read_lane_u64(best[e], (B - 1) & 63);  // all ones while best is not full
     dk = (nb < B) ? INFINITY : key_d(last_best);
     const float xi = tau * fminf(d1, dnn);
     thr_now = (nb == 0) ? INFINITY : dk + xi;
@@ -191,12 +199,36 @@ struct RegCache {
     if (lane >= cap) L = kEmptyKey;
     if (pos < cap && n < cap) n++;
   }
+  // the same for best, which may span several registers: what leaves lane 63 of one register
+  // enters lane 0 of the next
+  __device__ void best_insert(u64 key) {
+    const int lane = lane_id();
+    bool lt[NB];
+    int pos = 0;
+#pragma unroll
+    for (int e = 0; e < NB; e++) {
+      lt[e] = best[e] < key;
+      pos += __popcll(__ballot(lt[e]));
+    }
+    if (pos >= B) return;
+    u64 carry = key;
+#pragma unroll
+    for (int e = 0; e < NB; e++) {
+      const u64 leaving = (e + 1 < NB) ? read_lane_u64(best[e], 63) : 0;
+      const u64 up = wave_shift_up(best[e], carry);
+      const int gi = e * kWave + lane;
+      best[e] = lt[e] ? best[e] : (gi == pos ? key : up);
+      if (gi >= B) best[e] = kEmptyKey;
+      carry = leaving;
+    }
+    if (nb < B) nb++;
+  }
   // Alg. 2 Push (the key is known not to be in either list).  Most accepted candidates lie
   // between the k-th best distance and the threshold: they enter prioq only, so best (and the
   // bounds derived from it) is touched only when the key really belongs there.
   __device__ void push(u64 key) {
     if (nb < B || key < last_best) {
-      list_insert(best, nb, B, key);
+      best_insert(key);
       refresh_bounds();
     }
     list_insert(pq, np, P, key);
@@ -227,21 +259,30 @@ struct RegCache {
   // Alg. 4 Transform (see the LDS variant in ggnn_device.h for the reading); staged through LDS
   __device__ void transform(const int32_t* __restrict__ table) {
     const int lane = lane_id();
-    u64* sb = stage; u64* sp = stage + 64; u64* out = stage + 128;
-    if (lane < nb) best = (best & 0xFFFFFFFF00000000ull) | (uint32_t)table[key_id(best)];
+    u64* sb = stage; u64* sp = stage + NB * 64; u64* out = stage + (NB + 1) * 64;
+#pragma unroll
+    for (int e = 0; e < NB; e++) {
+      const int gi = e * kWave + lane;
+      if (gi < nb) best[e] = (best[e] & 0xFFFFFFFF00000000ull) | (uint32_t)table[key_id(best[e])];
+      sb[gi] = best[e];
+    }
     if (lane < np) pq = (pq & 0xFFFFFFFF00000000ull) | (uint32_t)table[key_id(pq)];
-    sb[lane] = best;
     wave_sync();
     // best: same distances, ties re-ordered by the new ids
-    if (lane < nb) {
-      int r = 0;
-      for (int j = 0; j < nb; j++) r += sb[j] < best;
-      out[r] = best;
+#pragma unroll
+    for (int e = 0; e < NB; e++) {
+      if (e * kWave + lane < nb) {
+        int r = 0;
+        for (int j = 0; j < nb; j++) r += sb[j] < best[e];
+        out[r] = best[e];
+      }
     }
     wave_sync();
-    best = (lane < nb) ? out[lane] : kEmptyKey;
+#pragma unroll
+    for (int e = 0; e < NB; e++) best[e] = (e * kWave + lane < nb) ? out[e * kWave + lane] : kEmptyKey;
     wave_sync();
-    sb[lane] = best;
+#pragma unroll
+    for (int e = 0; e < NB; e++) sb[e * kWave + lane] = best[e];
     // prioq entries that are also in best are dropped from the union
     bool dup = false;
     if (lane < np)
@@ -250,13 +291,19 @@ struct RegCache {
     wave_sync();
     const int m = nb + __popcll(__ballot(lane < np && !dup));
     // rank of every entry in the union; the P smallest form the new prioq
-    int rb = lane, rp = 0;
-    for (int j = 0; j < np; j++) rb += sp[j] < best;
+    int rb[NB], rp = 0;
+#pragma unroll
+    for (int e = 0; e < NB; e++) {
+      rb[e] = e * kWave + lane;
+      for (int j = 0; j < np; j++) rb[e] += sp[j] < best[e];
+    }
     const u64 mine = sp[lane];
     for (int j = 0; j < nb; j++) rp += sb[j] < mine;
     for (int j = 0; j < np; j++) rp += sp[j] < mine;
     wave_sync();
-    if (lane < nb && rb < kWave) out[rb] = best;
+#pragma unroll
+    for (int e = 0; e < NB; e++)
+      if (e * kWave + lane < nb && rb[e] < kWave) out[rb[e]] = best[e];
     if (mine != kEmptyKey && rp < kWave) out[rp] = mine;
     wave_sync();
     np = m < P ? m : P;
@@ -264,9 +311,12 @@ struct RegCache {
     iter = 0;
     if (nb > 0) refresh_bounds();
     listed_clear();
-    if (lane < nb) {
-      const uint32_t h = listed_bucket(key_id(best));
-      atomicOr(&listed_bits[h >> 5], 1u << (h & 31));
+#pragma unroll
+    for (int e = 0; e < NB; e++) {
+      if (e * kWave + lane < nb) {
+        const uint32_t h = listed_bucket(key_id(best[e]));
+        atomicOr(&listed_bits[h >> 5], 1u << (h & 31));
+      }
     }
     if (lane < np) {
       const uint32_t h = listed_bucket(key_id(pq));
@@ -302,7 +352,10 @@ struct RegCache {
       const int j = __builtin_ctzll(cand);
       cand &= cand - 1;
       const int32_t pid = __builtin_amdgcn_readlane(p, j);
-      if (__ballot(key_id(best) == pid || key_id(pq) == pid)) known |= 1ull << j;
+      bool hit = key_id(pq) == pid;
+#pragma unroll
+      for (int e = 0; e < NB; e++) hit = hit || key_id(best[e]) == pid;
+      if (__ballot(hit)) known |= 1ull << j;
     }
     alive = alive && !((known >> lane) & 1);
     GGNN_TICK(3);  // membership in best / prioq
@@ -375,22 +428,33 @@ struct RegCache {
   // results
   __device__ void store_results(int k, int32_t* __restrict__ ids, float* __restrict__ dists) const {
     const int lane = lane_id();
-    for (int j = lane; j < k; j += kWave) {
-      const u64 key = (j < kWave) ? best : kEmptyKey;  // k > 64 cannot hold more than 64 results
-      const bool ok = j < nb;
-      ids[j] = ok ? key_id(key) : -1;
-      dists[j] = ok ? key_d(key) : INFINITY;
+#pragma unroll
+    for (int e = 0; e < NB; e++) {
+      const int j = e * kWave + lane;
+      if (j < k) {
+        ids[j] = (j < nb) ? key_id(best[e]) : -1;
+        dists[j] = (j < nb) ? key_d(best[e]) : INFINITY;
+      }
+    }
+    for (int j = NB * kWave + lane; j < k; j += kWave) {  // best cannot hold that many
+      ids[j] = -1;
+      dists[j] = INFINITY;
     }
   }
   __device__ void store_row(int K, int32_t* __restrict__ out) const {
     const int lane = lane_id();
-    if (lane < K) out[lane] = (lane < nb) ? key_id(best) : -1;
+    if (lane < K) out[lane] = (lane < nb) ? key_id(best[0]) : -1;  // K <= 64
   }
   __device__ void store_prefs(u64* __restrict__ pref, int32_t* __restrict__ npref) const {
     const int lane = lane_id();
-    if (lane < nb) pref[lane] = best;
+#pragma unroll
+    for (int e = 0; e < NB; e++)
+      if (e * kWave + lane < nb) pref[e * kWave + lane] = best[e];
     if (lane == 0) *npref = nb;
   }
 };
+
+using RegCache = RegCacheT<1>;   // best of at most 64 entries
+using RegCache2 = RegCacheT<2>;  // best of at most 128 entries
 
 }  // namespace ggnn

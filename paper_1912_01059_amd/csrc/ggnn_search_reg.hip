@@ -1,4 +1,5 @@
-// Search kernels with best and prioq held in registers (capacities of at most 64 each).
+// Search kernels with best and prioq held in registers (prioq of at most 64 entries, best of at
+// most 64, or 128 for user queries).
 #include "ggnn_search_kernels.h"
 
 namespace ggnn {
@@ -6,6 +7,11 @@ hipError_t launch_query_reg(const GraphDev& G, int dtype, int metric, const void
                             const SearchParams& sp, int every_layer, int32_t* ids, float* dists, uint32_t* counters,
                             hipStream_t stream) {
   return launch_query_t<RegCache>(G, dtype, metric, queries, Q, k, sp, every_layer, ids, dists, counters, stream);
+}
+hipError_t launch_query_reg2(const GraphDev& G, int dtype, int metric, const void* queries, int64_t Q, int k,
+                             const SearchParams& sp, int every_layer, int32_t* ids, float* dists, uint32_t* counters,
+                             hipStream_t stream) {
+  return launch_query_t<RegCache2>(G, dtype, metric, queries, Q, k, sp, every_layer, ids, dists, counters, stream);
 }
 hipError_t launch_merge_reg(const GraphDev& G, int dtype, int metric, int l_top, int l_m, const SearchParams& sp,
                             int32_t* out_rows, float* dnn1, unsigned long long* work, hipStream_t stream) {

@@ -60,13 +60,14 @@ def check_counters(cnt, rcnt):
 # ------------------------------------------------------------------------------ query
 
 @pytest.mark.parametrize("every_layer", [False, True])
-@pytest.mark.parametrize("k,beam,tau", [(10, 10, 0.0), (10, 10, 0.3), (10, 64, 0.5), (1, 10, 0.4), (24, 24, 0.2)])
+@pytest.mark.parametrize("k,beam,tau", [(10, 10, 0.0), (10, 10, 0.3), (10, 64, 0.5), (1, 10, 0.4), (24, 24, 0.2),
+                                         (100, 100, 0.3), (10, 128, 0.1), (70, 65, 0.2), (130, 130, 0.2)])
 def test_query_matches_oracle_on_config1(ggnn, R, sift10k, sift10k_oracle_graph, every_layer, k, beam, tau):
     base, queries, cfg = sift10k
     og = sift10k_oracle_graph
     g = to_gpu_graph(ggnn, og, dev(base))
-    ids, d, cnt = g.query(dev(queries), k, beam, tau, every_layer=every_layer, counters=True)
-    rids, rd, rcnt = og.query(queries, k, beam, tau, every_layer=every_layer, counters=True)
+    ids, d, cnt = g.query(dev(queries), k, beam, tau, visited_cap=384, every_layer=every_layer, counters=True)
+    rids, rd, rcnt = og.query(queries, k, beam, tau, visited_cap=384, every_layer=every_layer, counters=True)
     assert_same_results(ids, d, rids, rd)
     check_counters(cnt, rcnt)
 

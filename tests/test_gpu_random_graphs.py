@@ -52,7 +52,7 @@ def _random_case(seed):
         queries = rng.integers(0, 256, (Q, D)).astype(np.float32)
         queries[: Q // 3] = base[rng.integers(0, N, Q // 3)]  # queries that coincide with base rows
     k = int(rng.integers(1, 20))
-    beam = int(rng.integers(1, 70))
+    beam = int(rng.integers(1, 70)) if rng.random() < 0.6 else int(rng.integers(65, 140))
     P = int(rng.integers(1, 80)) if rng.random() < 0.8 else int(rng.integers(80, 200))
     V = int(rng.integers(1, 300))
     it = int(rng.integers(1, V + 1))
