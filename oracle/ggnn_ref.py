@@ -27,7 +27,8 @@ def default_params(tau_build=0.5, refinements=2, pq_cap=64, visited_cap=384, max
 def lib():
     global _lib
     if _lib is None:
-        path = build_oracle.build(force=False)
+        # GGNN_REF_LIB: an alternative build of the oracle (used by the mutation checks of the pins)
+        path = os.environ.get("GGNN_REF_LIB") or build_oracle.build(force=False)
         L = C.CDLL(path)
         vp, i64, i32, f32 = C.c_void_p, C.c_int64, C.c_int32, C.c_float
         L.ggnn_ref_geometry.argtypes = [i64, C.c_int, C.c_int, vp, vp, vp]
