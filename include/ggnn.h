@@ -139,6 +139,14 @@ int ggnn_query_ex(const ggnn_graph* g, const void* queries_dev, int64_t Q, int32
                   int32_t pq_cap, int32_t visited_cap, int32_t max_iter, int32_t every_layer, void* stream,
                   int32_t* ids_dev, float* dists_dev, uint32_t* counters_dev, int32_t asynchronous);
 
+/* Alg. 1 on the bottom layer alone, from start points the caller names instead of the top layer:
+ * the search of a flat graph (import its rows as layer 0; the upper layers are not touched), or the
+ * start-point comparison of the paper's appendix "Query Starting Points" (centroid, worst point).
+ * start_ids_dev: n_start (1..64) distinct base rows, device.  Everything else as ggnn_query_ex. */
+int ggnn_query_from(const ggnn_graph* g, const void* queries_dev, int64_t Q, int32_t k, int32_t beam, float slack,
+                    int32_t pq_cap, int32_t visited_cap, int32_t max_iter, const int32_t* start_ids_dev, int32_t n_start,
+                    void* stream, int32_t* ids_dev, float* dists_dev, uint32_t* counters_dev, int32_t asynchronous);
+
 /* ---- sharding on one GPU (Sec. 4.5) -------------------------------------------------- */
 
 /* Merges the answers S independent shards gave to the same Q queries.  ids_dev / dists_dev:

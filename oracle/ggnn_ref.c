@@ -497,6 +497,15 @@ static void cache_descend(cache_t* c, int layer) {
 int ggnn_ref_query(const ggnn_ref_graph* g, const void* queries, int64_t Q, int k,
                    int B, float tau, int P, int V, int max_iter, int every_layer,
                    int32_t* ids, float* dists, uint32_t* counters) {
+  return ggnn_ref_query_from(g, queries, Q, k, B, tau, P, V, max_iter, every_layer, NULL, 0, ids, dists, counters);
+}
+
+/* The same with explicit start points: when `start` is given, Alg. 1 runs on the bottom layer alone
+ * from those points (a flat graph; appendix "Query Starting Points"). */
+int ggnn_ref_query_from(const ggnn_ref_graph* g, const void* queries, int64_t Q, int k,
+                        int B, float tau, int P, int V, int max_iter, int every_layer,
+                        const int32_t* start_ids, int n_start,
+                        int32_t* ids, float* dists, uint32_t* counters) {
   if (!g || !queries || k < 1 || B < k || P < 1 || V < 1 || max_iter < 0) return -1;
   int top = g->L - 1;
   int err = 0;
@@ -513,6 +522,10 @@ int ggnn_ref_query(const ggnn_ref_graph* g, const void* queries, int64_t Q, int 
     int32_t start[1024];
     int ns = (int)g->n[top];
     for (int i = 0; i < ns; i++) start[i] = i;
+    if (start_ids) {
+      cache_fetch(&c, 0, start_ids, n_start);
+      cache_descend(&c, 0);
+    } else {
     cache_fetch(&c, top, start, ns);
     if (every_layer) {
       /* Alg. 4: search every layer below the top one in turn */
@@ -524,6 +537,7 @@ int ggnn_ref_query(const ggnn_ref_graph* g, const void* queries, int64_t Q, int 
       /* Sec. 4.4: continue directly on the bottom layer */
       cache_transform(&c, g->to_base[top]);
       cache_descend(&c, 0);
+    }
     }
     for (int j = 0; j < k; j++) {
       ids[qi * k + j] = (j < c.nb) ? c.best[j].id : -1;

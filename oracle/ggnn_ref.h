@@ -97,6 +97,13 @@ int ggnn_ref_query(const ggnn_ref_graph* g, const void* queries, int64_t Q, int 
 int ggnn_ref_merge_shards(int S, int64_t Q, int k, const int32_t* ids, const float* dists,
                           const int32_t* offsets, int32_t* out_ids, float* out_dists);
 
+/* Alg. 1 on the bottom layer alone from the given start points (start_ids != NULL), else as
+ * ggnn_ref_query. */
+int ggnn_ref_query_from(const ggnn_ref_graph* g, const void* queries, int64_t Q, int k,
+                        int B, float tau, int P, int V, int max_iter, int every_layer,
+                        const int32_t* start_ids, int n_start,
+                        int32_t* ids, float* dists, uint32_t* counters);
+
 int ggnn_ref_num_threads(void);
 
 #ifdef __cplusplus

@@ -64,6 +64,7 @@ def lib():
         L.ggnn_ref_build.argtypes = [vp, C.POINTER(BuildParams)]
         L.ggnn_ref_query.argtypes = [vp, vp, i64, C.c_int, C.c_int, f32, C.c_int, C.c_int, C.c_int, C.c_int, vp, vp, vp]
         L.ggnn_ref_num_threads.restype = C.c_int
+        L.ggnn_ref_query_from.argtypes = [vp, vp, i64, C.c_int, C.c_int, f32, C.c_int, C.c_int, C.c_int, C.c_int, vp, C.c_int, vp, vp, vp]
         L.ggnn_ref_merge_shards.argtypes = [C.c_int, i64, C.c_int, vp, vp, vp, vp, vp]
         _lib = L
     return _lib
@@ -191,7 +192,7 @@ class Graph:
         return self
 
     def query(self, queries, k, beam, slack, pq_cap=64, visited_cap=384, max_iter=None, every_layer=False,
-              counters=False):
+              counters=False, start_ids=None):
         queries = np.ascontiguousarray(queries)
         assert queries.dtype == self.base.dtype
         Q = queries.shape[0]
@@ -200,8 +201,9 @@ class Graph:
         ids = np.empty((Q, k), np.int32)
         dists = np.empty((Q, k), np.float32)
         cnt = np.zeros((Q, 2), np.uint32) if counters else None
-        rc = lib().ggnn_ref_query(self.h, _ptr(queries), Q, k, B, slack, pq_cap, visited_cap, max_iter,
-                                  1 if every_layer else 0,
+        st = None if start_ids is None else np.ascontiguousarray(start_ids, np.int32)
+        rc = lib().ggnn_ref_query_from(self.h, _ptr(queries), Q, k, B, slack, pq_cap, visited_cap, max_iter,
+                                  1 if every_layer else 0, None if st is None else _ptr(st), 0 if st is None else len(st),
                                   _ptr(ids), _ptr(dists), _ptr(cnt) if counters else None)
         if rc != 0:
             raise RuntimeError("query failed: %d" % rc)

@@ -44,7 +44,7 @@ class BuildTimes(C.Structure):
 
 EXPORTS = [
     "ggnn_build", "ggnn_build_ex", "ggnn_graph_create", "ggnn_select", "ggnn_merge", "ggnn_sym",
-    "ggnn_build_steps", "ggnn_build_get_times", "ggnn_query", "ggnn_query_ex", "ggnn_graph_info",
+    "ggnn_build_steps", "ggnn_build_get_times", "ggnn_query", "ggnn_query_ex", "ggnn_query_from", "ggnn_graph_info",
     "ggnn_graph_export", "ggnn_graph_import", "ggnn_graph_export_dnn", "ggnn_graph_import_dnn",
     "ggnn_graph_export_inv_count", "ggnn_set_cache_mode", "ggnn_gather_probe", "ggnn_merge_shards", "ggnn_free", "ggnn_last_error",
 ]
@@ -69,6 +69,7 @@ def lib():
         L.ggnn_build_get_times.argtypes = [vp, C.POINTER(BuildTimes)]
         L.ggnn_query.argtypes = [vp, vp, i64, i32, i32, f32, vp, vp]
         L.ggnn_query_ex.argtypes = [vp, vp, i64, i32, i32, f32, i32, i32, i32, i32, vp, vp, vp, vp, i32]
+        L.ggnn_query_from.argtypes = [vp, vp, i64, i32, i32, f32, i32, i32, i32, vp, i32, vp, vp, vp, vp, i32]
         L.ggnn_graph_info.argtypes = [vp, C.POINTER(GraphDesc)]
         L.ggnn_graph_export.argtypes = [vp, i32, vp, vp, vp]
         L.ggnn_graph_import.argtypes = [vp, i32, vp, vp, vp]
@@ -251,9 +252,9 @@ class Graph:
         return c
 
     def query(self, queries, k, beam, slack, pq_cap=0, visited_cap=0, max_iter=0, every_layer=False,
-              counters=False, out=None, stream=None, asynchronous=False):
+              counters=False, out=None, stream=None, asynchronous=False, start_ids=None):
         return query(self, queries, k, beam, slack, pq_cap, visited_cap, max_iter, every_layer, counters, out,
-                     stream, asynchronous)
+                     stream, asynchronous, start_ids)
 
 
 def graph_create(base, K, levels, seed=42, metric=L2, segment_size=0, tau_build=0.0, refinements=2, pq_cap=0,
@@ -275,7 +276,7 @@ def build(base, K, levels, seed=42, metric=L2, segment_size=0, tau_build=0.0, re
 
 
 def query(graph, queries, k, beam, slack, pq_cap=0, visited_cap=0, max_iter=0, every_layer=False,
-          counters=False, out=None, stream=None, asynchronous=False):
+          counters=False, out=None, stream=None, asynchronous=False, start_ids=None):
     """ggnn_query_ex.  Returns (ids, dists[, counters]) as GPU tensors; `out` = (ids, dists) reuses buffers."""
     import torch
     Q = queries.shape[0]
@@ -287,6 +288,11 @@ def query(graph, queries, k, beam, slack, pq_cap=0, visited_cap=0, max_iter=0, e
     cnt = torch.zeros((Q, 4), dtype=torch.int32, device=queries.device) if counters else None
     if stream is None:
         stream = torch.cuda.current_stream().cuda_stream
+    if start_ids is not None:  # ggnn_query_from: bottom layer only, from the given start points
+        _check(lib().ggnn_query_from(graph.h, _dev_ptr(queries), Q, k, beam, slack, pq_cap, visited_cap, max_iter,
+                                     _dev_ptr(start_ids), start_ids.shape[0], C.c_void_p(stream), _dev_ptr(ids),
+                                     _dev_ptr(dists), _dev_ptr(cnt) if counters else None, 1 if asynchronous else 0))
+        return (ids, dists, cnt) if counters else (ids, dists)
     _check(lib().ggnn_query_ex(graph.h, _dev_ptr(queries), Q, k, beam, slack, pq_cap, visited_cap, max_iter,
                                1 if every_layer else 0, C.c_void_p(stream), _dev_ptr(ids), _dev_ptr(dists),
                                _dev_ptr(cnt) if counters else None, 1 if asynchronous else 0))

@@ -150,6 +150,7 @@ int make_search_params(int B, int P, int V, int max_iter, float tau, float dnn, 
   sp->H = next_pow2(2 * (max_iter > 0 ? max_iter : 1));
   if (sp->H < 64) sp->H = 64;
   sp->tau = tau; sp->dnn = dnn;
+  sp->start = nullptr; sp->n_start = 0;
   const int slots = register_slots(*sp, user_query);
   const size_t need = slots == 1 ? RegCache::lds_bytes(*sp) : slots == 2 ? RegCache2::lds_bytes(*sp) : LdsCache::lds_bytes(*sp);
   if (need > kMaxLds)
@@ -488,9 +489,10 @@ int ggnn_build_get_times(const ggnn_graph* g, ggnn_build_times* out) {
   return GGNN_OK;
 }
 
-int ggnn_query_ex(const ggnn_graph* g, const void* queries_dev, int64_t Q, int32_t k, int32_t beam, float slack,
-                  int32_t pq_cap, int32_t visited_cap, int32_t max_iter, int32_t every_layer, void* stream,
-                  int32_t* ids_dev, float* dists_dev, uint32_t* counters_dev, int32_t asynchronous) {
+static int query_impl(const ggnn_graph* g, const void* queries_dev, int64_t Q, int32_t k, int32_t beam, float slack,
+                      int32_t pq_cap, int32_t visited_cap, int32_t max_iter, int32_t every_layer,
+                      const int32_t* start_ids_dev, int32_t n_start, void* stream, int32_t* ids_dev, float* dists_dev,
+                      uint32_t* counters_dev, int32_t asynchronous) {
   if (!g) return fail(GGNN_ERR_INVALID, "graph is NULL");
   if (Q < 0 || Q > 0x7FFFFFFFll) return fail(GGNN_ERR_INVALID, "Q = %lld outside [0, 2^31)", (long long)Q);
   if (Q == 0) return GGNN_OK;
@@ -507,12 +509,40 @@ int ggnn_query_ex(const ggnn_graph* g, const void* queries_dev, int64_t Q, int32
   int rc = make_search_params(B, P, V, it, slack, g->stats[1], &sp, true);
   if (rc != GGNN_OK) return rc;
   hipStream_t st = stream ? (hipStream_t)stream : g->stream;
+  if (start_ids_dev) {
+    if (n_start < 1 || n_start > kWave) return fail(GGNN_ERR_INVALID, "n_start = %d outside [1, 64]", n_start);
+    // the kernel trusts the start points: check them here (a small synchronous copy)
+    int32_t host[kWave];
+    HIP_TRY(hipMemcpy(host, start_ids_dev, sizeof(int32_t) * n_start, hipMemcpyDeviceToHost));
+    for (int i = 0; i < n_start; i++) {
+      if (host[i] < 0 || host[i] >= g->N) return fail(GGNN_ERR_INVALID, "start point %d = %d outside [0, N)", i, host[i]);
+      for (int j = 0; j < i; j++)
+        if (host[j] == host[i]) return fail(GGNN_ERR_INVALID, "start point %d is listed twice", host[i]);
+    }
+    sp.start = start_ids_dev;
+    sp.n_start = n_start;
+  }
   GraphDev G = device_view(g);
   if (g->metric == GGNN_COSINE && g->dtype != GGNN_F32) return fail(GGNN_ERR_INVALID, "cosine needs float32 queries");
   HIP_TRY(launch_query(G, row_dtype(g), g->metric, queries_dev, Q, k, sp, every_layer ? 1 : 0, ids_dev, dists_dev,
                        counters_dev, st));
   if (!asynchronous) HIP_TRY(hipStreamSynchronize(st));
   return GGNN_OK;
+}
+
+int ggnn_query_ex(const ggnn_graph* g, const void* queries_dev, int64_t Q, int32_t k, int32_t beam, float slack,
+                  int32_t pq_cap, int32_t visited_cap, int32_t max_iter, int32_t every_layer, void* stream,
+                  int32_t* ids_dev, float* dists_dev, uint32_t* counters_dev, int32_t asynchronous) {
+  return query_impl(g, queries_dev, Q, k, beam, slack, pq_cap, visited_cap, max_iter, every_layer, nullptr, 0, stream,
+                    ids_dev, dists_dev, counters_dev, asynchronous);
+}
+
+int ggnn_query_from(const ggnn_graph* g, const void* queries_dev, int64_t Q, int32_t k, int32_t beam, float slack,
+                    int32_t pq_cap, int32_t visited_cap, int32_t max_iter, const int32_t* start_ids_dev, int32_t n_start,
+                    void* stream, int32_t* ids_dev, float* dists_dev, uint32_t* counters_dev, int32_t asynchronous) {
+  if (!start_ids_dev) return fail(GGNN_ERR_INVALID, "start_ids_dev is NULL");
+  return query_impl(g, queries_dev, Q, k, beam, slack, pq_cap, visited_cap, max_iter, 0, start_ids_dev, n_start, stream,
+                    ids_dev, dists_dev, counters_dev, asynchronous);
 }
 
 int ggnn_query(const ggnn_graph* g, const void* queries_dev, int64_t Q, int32_t k, int32_t beam, float slack,

@@ -35,6 +35,8 @@ struct SearchParams {
   int32_t B, P, H;     // best length, prioq capacity, hash slots (power of two >= 2*max_iter)
   int32_t max_iter;
   float tau, dnn;
+  const int32_t* start;  // user queries only: explicit start points on the bottom layer, or null
+  int32_t n_start;
 };
 
 // ---- packed keys: (float32 distance, int32 id) ordered as one unsigned 64-bit integer.

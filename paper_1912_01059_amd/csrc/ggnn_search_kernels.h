@@ -55,8 +55,14 @@ __global__ __launch_bounds__(kWave) void query_kernel(GraphDev G, const uint8_t*
   load_query<DT, NCH>(q, queries + (size_t)qi * (size_t)G.row_bytes, G.nchunks);
   if (METRIC == 1) normalise_query<DT, NCH>(q);
 
-  // start points: the s points of the top layer (Sec. 3.1, Sec. 4.4)
   const int top = G.L - 1;
+  if (sp.start) {
+    // Alg. 1 on the bottom layer alone, from start points the caller chose (a flat graph, or the
+    // start-point comparison of the paper's appendix)
+    c.template fetch<DT, NCH, METRIC, kPasses>(G, 0, lane < sp.n_start ? sp.start[lane] : -1, q, -1);
+    descend<C, DT, NCH, METRIC>(c, G, 0, q, -1);
+  } else {
+  // start points: the s points of the top layer (Sec. 3.1, Sec. 4.4)
   c.template fetch<DT, NCH, METRIC, kPasses>(G, top, lane < G.s ? lane : -1, q, -1);
   if (every_layer) {
     for (int l = top - 1; l >= 0; l--) {
@@ -66,6 +72,7 @@ __global__ __launch_bounds__(kWave) void query_kernel(GraphDev G, const uint8_t*
   } else {
     c.transform(G.to_base[top]);
     descend<C, DT, NCH, METRIC>(c, G, 0, q, -1);
+  }
   }
   c.store_results(k, ids + (size_t)qi * k, dists + (size_t)qi * k);
 #ifdef GGNN_PHASE_TIMING

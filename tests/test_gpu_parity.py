@@ -341,3 +341,25 @@ def test_sharded_index_recall(ggnn, R, sift10k, sift10k_gt):
     got = ids.cpu().numpy()
     d2 = ((base[got[0]].astype(np.int64) - queries[0].astype(np.int64)) ** 2).sum(1)
     assert np.array_equal(d.cpu().numpy()[0], np.sqrt(d2.astype(np.float32)))
+
+
+# ------------------------------------------------------------------------------ explicit start points
+
+def test_query_from_start_points(ggnn, R, sift10k, sift10k_oracle_graph):
+    """Centroid / worst-point starts of the paper's appendix on config 1, and argument checks."""
+    base, queries, cfg = sift10k
+    og = sift10k_oracle_graph
+    g = to_gpu_graph(ggnn, og, dev(base))
+    centre = base.mean(0)
+    d2 = ((base - centre) ** 2).sum(1)
+    for starts in (np.array([d2.argmin()], np.int32), np.array([d2.argmax()], np.int32),
+                   np.arange(0, 6400, 100, dtype=np.int32)):
+        ids, d = g.query(dev(queries), 10, 10, 0.4, start_ids=dev(starts))
+        rids, rd = og.query(queries, 10, 10, 0.4, start_ids=starts)
+        assert_same_results(ids, d, rids, rd)
+    with pytest.raises(ggnn.GgnnError):
+        g.query(dev(queries[:4]), 10, 10, 0.4, start_ids=dev(np.array([5, 5], np.int32)))
+    with pytest.raises(ggnn.GgnnError):
+        g.query(dev(queries[:4]), 10, 10, 0.4, start_ids=dev(np.array([10_000], np.int32)))
+    with pytest.raises(ggnn.GgnnError):
+        g.query(dev(queries[:4]), 10, 10, 0.4, start_ids=dev(np.arange(65, dtype=np.int32)))

@@ -94,5 +94,15 @@ def test_search_matches_oracle_on_random_graph(seed, mode):
             assert np.array_equal(ids.cpu().numpy(), rids), info
             assert np.array_equal(d.cpu().numpy().view(np.uint32), rd.view(np.uint32)), info
             assert np.array_equal(cnt.cpu().numpy().astype(np.uint32)[:, :2], rcnt), info
+        # bottom layer alone, from start points of the caller's choice
+        rng = np.random.default_rng(seed + 1000)
+        starts = rng.choice(c["N"], int(rng.integers(1, min(64, c["N"]) + 1)), replace=False).astype(np.int32)
+        ids, d, cnt = g.query(q, c["k"], c["beam"], c["tau"], pq_cap=c["P"], visited_cap=c["V"], max_iter=c["it"],
+                              counters=True, start_ids=torch.from_numpy(starts).cuda())
+        rids, rd, rcnt = og.query(c["queries"], c["k"], c["beam"], c["tau"], pq_cap=c["P"], visited_cap=c["V"],
+                                  max_iter=c["it"], counters=True, start_ids=starts)
+        assert np.array_equal(ids.cpu().numpy(), rids), "start points, seed %d" % seed
+        assert np.array_equal(d.cpu().numpy().view(np.uint32), rd.view(np.uint32))
+        assert np.array_equal(cnt.cpu().numpy().astype(np.uint32)[:, :2], rcnt)
     finally:
         ggnn.set_cache_mode(0)

@@ -541,3 +541,27 @@ def test_shard_merge_equals_search_over_the_whole_set():
     dists[0][:, 3:] = np.inf
     mi2, md2 = R.merge_shards(np.stack(ids), np.stack(dists), bounds[:-1])
     assert (mi2 >= 0).all() and (np.diff(md2, axis=1) >= 0).all()
+
+
+# ---------------------------------------------------------------- explicit start points
+
+@pytest.mark.parametrize("seed", [31, 32])
+def test_search_from_given_start_points_is_classical_best_first(seed):
+    """A flat graph searched from start points of the caller's choice (appendix 'Query Starting
+    Points'): with tau = 0 and ample capacities this is the textbook best-first search again."""
+    N, D, K = 300, 20, 8
+    g, base = _tiny_graph(N, D, K, seed)
+    rng = np.random.default_rng(seed)
+    q = rng.standard_normal((20, D)).astype(np.float32)
+    starts = rng.choice(N, 5, replace=False).astype(np.int32)
+    ids, dists = g.query(q, 10, 16, 0.0, pq_cap=N, visited_cap=N, max_iter=N, start_ids=starts)
+    for i in range(len(q)):
+        want_ids, want_d = _classical_best_first(base, g.edges(0), starts.tolist(), q[i], 16)
+        assert ids[i].tolist() == want_ids[:10]
+        assert np.array_equal(dists[i], np.array(want_d[:10], np.float32))
+    # starting everywhere with an unbounded best list is exhaustive search
+    every = np.arange(64, dtype=np.int32)
+    g2, base2 = _tiny_graph(64, D, K, seed + 100)
+    ids2, d2 = g2.query(q, 5, 64, 0.0, pq_cap=64, visited_cap=64, max_iter=64, start_ids=every)
+    gi, gd = R.bruteforce(base2, q, 5)
+    assert np.array_equal(ids2, gi) and np.array_equal(d2, gd)
