@@ -55,7 +55,7 @@ def lib():
     global _lib
     if _lib is None:
         if not os.path.exists(_LIB_PATH):
-            raise GgnnError("%s is missing: run `python -m paper_1912_01059_amd.build` (or __graft_entry__.build())"
+            raise GgnnError("%s is missing: run `python -m paper_1912_01059_amd.hipbuild` (or __graft_entry__.build())"
                             % _LIB_PATH)
         L = C.CDLL(_LIB_PATH)
         vp, i64, i32, u64, f32 = C.c_void_p, C.c_int64, C.c_int32, C.c_uint64, C.c_float

@@ -24,8 +24,8 @@ def test_library_exports_every_declared_symbol():
     from paper_1912_01059_amd import binding
     path = os.path.join(ROOT, "paper_1912_01059_amd", "libggnn.so")
     if not os.path.exists(path):
-        from paper_1912_01059_amd import build
-        build.build()
+        from paper_1912_01059_amd import hipbuild
+        hipbuild.build()
     lib = ctypes.CDLL(path)
     for name in _declared():
         assert hasattr(lib, name), name
