@@ -64,6 +64,9 @@ def main():
                     help="also run a plain 1 GiB device-to-device copy (reference for hardware byte counters)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=2000)
+    ap.add_argument("--cpu-exhaustive", type=int, default=64, help="queries of the oracle's timed exhaustive search (0 = skip)")
+    ap.add_argument("--cpu-build-n", type=int, default=10_000,
+                    help="points of the oracle's timed construction (0 = skip; above 10 000: a subset of the workload)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the method shards by replicating the graph "
@@ -239,9 +242,45 @@ def main():
         # the exhaustive search used for the recall figure, checked against the oracle's on a few queries
         _, bf_d = R.bruteforce(base_np, queries_np[:16], k, metric=R.COSINE if metric == ggnn.COSINE else R.L2)
         gt_ok = bool(np.allclose(bf_d, gt_d[:16].cpu().numpy(), rtol=2e-5, atol=1e-6))
-        cpu = {"value": round(ns / cpu_s, 1), "unit": "queries/s", "cores": R.lib().ggnn_ref_num_threads(),
+        cores = R.lib().ggnn_ref_num_threads()
+        cpu = {"value": round(ns / cpu_s, 1), "unit": "queries/s", "cores": cores,
                "kind": "oracle", "sample": "first %d of the %d queries, same graph and operating point" % (ns, Q),
                "identical_to_gpu": same, "ground_truth_matches_oracle_exhaustive_search": gt_ok}
+        # context figures (the paper's CPU references ran on one thread): the same search on one thread,
+        # the oracle's exhaustive search, and the oracle's construction of the small configuration
+        n1 = min(500, ns)
+        R.lib().ggnn_ref_set_num_threads(1)
+        t0 = time.perf_counter()
+        og.query(queries_np[:n1], k, chosen["beam"], chosen["slack"], pq_cap=chosen["pq_cap"],
+                 visited_cap=chosen["visited_cap"], every_layer=True)
+        cpu["single_thread"] = {"value": round(n1 / (time.perf_counter() - t0), 1), "unit": "queries/s", "cores": 1,
+                                "sample": "first %d queries" % n1}
+        R.lib().ggnn_ref_set_num_threads(cores)
+        nb = min(args.cpu_exhaustive, Q)
+        if nb > 0:
+            t0 = time.perf_counter()
+            R.bruteforce(base_np, queries_np[:nb], k, metric=R.COSINE if metric == ggnn.COSINE else R.L2)
+            cpu["exhaustive_search"] = {"value": round(nb / (time.perf_counter() - t0), 2), "unit": "queries/s",
+                                        "cores": cores, "sample": "first %d queries against all %d points" % (nb, N)}
+        if args.cpu_build_n > 0:
+            small_np, _, scfg = ggnn_inputs.make(args.workload if args.cpu_build_n > 10_000 else "sift10k",
+                                                 n=args.cpu_build_n, q=1)
+            sg = R.Graph(small_np, scfg["K"], 3, seed=42)
+            t0 = time.perf_counter()
+            sg.build(R.default_params(visited_cap=args.build_iter, max_iter=args.build_iter))
+            ob_s = time.perf_counter() - t0
+            sb = torch.from_numpy(small_np).to(dev)
+            ggnn.build(sb, scfg["K"], 3, seed=42, visited_cap=args.build_iter, max_iter=args.build_iter)  # warm-up
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            gg = ggnn.build(sb, scfg["K"], 3, seed=42, visited_cap=args.build_iter, max_iter=args.build_iter)
+            torch.cuda.synchronize()
+            gb_s = time.perf_counter() - t0
+            same_graph = all(np.array_equal(gg.export_layer(l)[0], sg.edges(l)) for l in range(3))
+            cpu["build"] = {"seconds": round(ob_s, 2), "cores": cores, "gpu_seconds": round(gb_s, 4),
+                            "graph_identical_to_gpu": bool(same_graph),
+                            "sample": "%d x %d points, K=%d, 3 levels, construction limit %d" % (
+                                small_np.shape[0], small_np.shape[1], scfg["K"], args.build_iter)}
 
     out = {
         "metric": "queries/s at Recall@10>=0.95 (1M x 128 L2, k=10)", "value": round(qps, 1), "unit": "queries/s",

@@ -23,6 +23,9 @@ CONFIGS = {
                    metric="l2", K=24, levels=4, k=10, beam=10, data_seed=1003, query_seed=2003),
     "glove1m": dict(kind="vmf", N=1_200_000, D=100, Q=10_000, components=2000, kappa=20.0, norm_sigma=0.5,
                     dtype="f32", metric="cosine", K=40, levels=4, k=10, beam=10, data_seed=1004, query_seed=2004),
+    # a high-dimensional configuration in the shape of GIST1M (960 floats per vector, 1 000 queries)
+    "gist1m": dict(kind="spectrum", N=1_000_000, D=960, Q=1_000, dtype="f32",
+                   metric="l2", K=24, levels=4, k=10, beam=10, data_seed=1006, query_seed=2006),
     "sift100m_u8": dict(kind="gmm", N=100_000_000, D=128, Q=10_000, components=65536, sigma=25.0, dtype="u8",
                         metric="l2", K=24, levels=4, k=10, beam=10, data_seed=1005, query_seed=2005),
 }

@@ -19,9 +19,11 @@
  *  - Distances are plain (not squared) Euclidean norms, or 1 - cos for GGNN_COSINE, in
  *    float32.  Every ordered result uses the total order (distance, id).
  *  - float32 sums follow one fixed order, so results are reproducible bit for bit: the
- *    row is cut into 16-byte chunks, chunk c belongs to lane c mod GGNN_ROW_LANES, a lane
- *    accumulates acc = fma(t, t, acc) over its chunks in ascending order, and the lanes
- *    are combined by a butterfly (distance 4, 2, 1).
+ *    row is cut into 16-byte chunks, chunk c belongs to lane c mod R, a lane accumulates
+ *    acc = fma(t, t, acc) over its chunks in ascending order, and the R lanes are combined
+ *    by a butterfly (distance R/2, ..., 2, 1).  R = GGNN_ROW_LANES for rows of at most 1024
+ *    bytes (for cosine: of the float32 unit-length copy), GGNN_WIDE_ROW_LANES for longer rows.
+ *  - Row lengths: a multiple of 16 bytes; float32 D <= 1024, uint8 D <= 256.
  */
 #ifndef GGNN_H
 #define GGNN_H
@@ -33,6 +35,7 @@ extern "C" {
 
 #define GGNN_MAX_LEVELS 8
 #define GGNN_ROW_LANES 8
+#define GGNN_WIDE_ROW_LANES 64
 
 typedef struct ggnn_graph ggnn_graph; /* opaque, owned by the library */
 

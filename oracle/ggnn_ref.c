@@ -55,6 +55,14 @@ int ggnn_ref_num_threads(void) {
 #endif
 }
 
+void ggnn_ref_set_num_threads(int n) {
+#ifdef _OPENMP
+  if (n >= 1) omp_set_num_threads(n);
+#else
+  (void)n;
+#endif
+}
+
 /* ------------------------------------------------------------------ hashing */
 
 static uint64_t mix64(uint64_t x) {

@@ -104,7 +104,9 @@ int ggnn_ref_query_from(const ggnn_ref_graph* g, const void* queries, int64_t Q,
                         const int32_t* start_ids, int n_start,
                         int32_t* ids, float* dists, uint32_t* counters);
 
+/* threads the OpenMP loops over queries / points use (timing aid; results do not depend on it) */
 int ggnn_ref_num_threads(void);
+void ggnn_ref_set_num_threads(int n);
 
 #ifdef __cplusplus
 }

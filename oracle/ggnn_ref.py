@@ -10,7 +10,15 @@ from . import build_oracle
 
 L2, COSINE = 0, 1
 F32, U8 = 0, 1
-ROW_LANES = 8  # accumulators of the fixed float32 summation tree (see ggnn_ref.c)
+ROW_LANES = 8        # accumulators of the fixed float32 summation tree (see ggnn_ref.c) ...
+WIDE_ROW_LANES = 64  # ... and for rows longer than 1024 bytes
+
+
+def row_lanes(D, itemsize, metric=0):
+    """Accumulators of the summation tree for rows of D elements: 8 for rows of at most 1024 bytes
+    (cosine: of the float32 unit-length copy), 64 beyond."""
+    row_bytes = D * (4 if metric == 1 else itemsize)
+    return ROW_LANES if row_bytes <= 1024 else WIDE_ROW_LANES
 
 _lib = None
 
@@ -64,6 +72,8 @@ def lib():
         L.ggnn_ref_build.argtypes = [vp, C.POINTER(BuildParams)]
         L.ggnn_ref_query.argtypes = [vp, vp, i64, C.c_int, C.c_int, f32, C.c_int, C.c_int, C.c_int, C.c_int, vp, vp, vp]
         L.ggnn_ref_num_threads.restype = C.c_int
+        L.ggnn_ref_set_num_threads.argtypes = [C.c_int]
+        L.ggnn_ref_set_num_threads.restype = None
         L.ggnn_ref_query_from.argtypes = [vp, vp, i64, C.c_int, C.c_int, f32, C.c_int, C.c_int, C.c_int, C.c_int, vp, C.c_int, vp, vp, vp]
         L.ggnn_ref_merge_shards.argtypes = [C.c_int, i64, C.c_int, vp, vp, vp, vp, vp]
         _lib = L
@@ -104,15 +114,17 @@ def uniform(seed, l_top, row):
     return lib().ggnn_ref_uniform(seed, l_top, row)
 
 
-def distance(q, row, metric=L2, lanes=ROW_LANES):
+def distance(q, row, metric=L2, lanes=None):
     q = np.ascontiguousarray(q, np.float32)
     row = np.ascontiguousarray(row)
+    lanes = lanes or row_lanes(q.shape[0], row.dtype.itemsize, metric)
     return float(lib().ggnn_ref_distance(_ptr(q), _ptr(row), q.shape[0], _dtype_code(row), metric, lanes))
 
 
-def bruteforce(base, queries, k, metric=L2, lanes=ROW_LANES):
+def bruteforce(base, queries, k, metric=L2, lanes=None):
     base = np.ascontiguousarray(base)
     queries = np.ascontiguousarray(queries)
+    lanes = lanes or row_lanes(base.shape[1], base.dtype.itemsize, metric)
     assert base.dtype == queries.dtype and base.shape[1] == queries.shape[1]
     Q = queries.shape[0]
     ids = np.empty((Q, k), np.int32)
@@ -128,9 +140,10 @@ class Graph:
     """Hierarchical kNN graph held by the oracle.  The arrays returned by the accessors
     are views into the oracle's memory (writable: tests use that to load a state)."""
 
-    def __init__(self, base, K, levels, s=32, metric=L2, seed=42, lanes=ROW_LANES):
+    def __init__(self, base, K, levels, s=32, metric=L2, seed=42, lanes=None):
         self.base = np.ascontiguousarray(base)
         self.N, self.D = self.base.shape
+        lanes = lanes or row_lanes(self.D, self.base.dtype.itemsize, metric)
         self.K, self.L, self.s, self.metric, self.seed, self.lanes = K, levels, s, metric, seed, lanes
         self.h = lib().ggnn_ref_graph_create(_ptr(self.base), self.N, self.D, K, levels, s,
                                              _dtype_code(self.base), metric, seed, lanes)

@@ -14,7 +14,7 @@
 
 using namespace ggnn;
 
-static_assert(GGNN_ROW_LANES == kRowLanes, "public constant and kernels disagree");
+static_assert(GGNN_ROW_LANES == kRowLanes && GGNN_WIDE_ROW_LANES == kWideRowLanes, "public constants and kernels disagree");
 static_assert(GGNN_MAX_LEVELS == kMaxLevels, "public constant and kernels disagree");
 
 namespace {
@@ -291,9 +291,8 @@ int ggnn_graph_create(const void* base_dev, int64_t N, int32_t D, int32_t K, int
   if (N < 2 || N > 0x7FFFFFFFll) return fail(GGNN_ERR_INVALID, "N = %lld outside [2, 2^31)", (long long)N);
   const int esize = dtype == GGNN_F32 ? 4 : 1;
   if (D < 1 || (D * esize) % 16 != 0) return fail(GGNN_ERR_INVALID, "a row of D = %d elements is not a multiple of 16 bytes", D);
-  const int need = (D * esize / 16 + kRowLanes - 1) / kRowLanes;
-  if ((dtype == GGNN_F32 && need > 8) || (dtype == GGNN_U8 && need > 2))
-    return fail(GGNN_ERR_INVALID, "D = %d too large (float32: <= 256, uint8: <= 256)", D);
+  if ((dtype == GGNN_F32 && D > 1024) || (dtype == GGNN_U8 && D > 256))
+    return fail(GGNN_ERR_INVALID, "D = %d too large (float32: <= 1024, uint8: <= 256)", D);
   if (((uintptr_t)base_dev) % 16 != 0) return fail(GGNN_ERR_INVALID, "base_dev is not 16-byte aligned");
 
   ggnn_graph* g = new (std::nothrow) ggnn_graph();

@@ -18,17 +18,18 @@ hipError_t launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t stream)
 }
 
 // unit-length float32 copy of the base rows (cosine): x / sqrt(sum x^2), the sum taken in
-// the fixed order of every distance; 8 lanes per row
+// the fixed order of every distance; RL lanes per row (8, or 64 for rows longer than 1024 bytes)
+template <int RL>
 __global__ __launch_bounds__(kWave) void normalise_kernel(const uint8_t* __restrict__ base, int dtype, int64_t N,
                                                           int D, float* __restrict__ out) {
-  const int lane = threadIdx.x, sub = lane & (kRowLanes - 1), grp = lane / kRowLanes;
-  const int64_t row = (int64_t)blockIdx.x * kRowsPerPass + grp;
+  const int lane = threadIdx.x, sub = lane & (RL - 1), grp = lane / RL;
+  const int64_t row = (int64_t)blockIdx.x * (kWave / RL) + grp;
   const bool act = row < N;
   const int per = (dtype == 1) ? 16 : 4;
   const int nchunks = (D + per - 1) / per;
   float acc = 0.0f;
   if (act) {
-    for (int chunk = sub; chunk < nchunks; chunk += kRowLanes) {
+    for (int chunk = sub; chunk < nchunks; chunk += RL) {
       for (int e = 0; e < per; e++) {
         int j = chunk * per + e;
         if (j >= D) break;
@@ -37,10 +38,10 @@ __global__ __launch_bounds__(kWave) void normalise_kernel(const uint8_t* __restr
       }
     }
   }
-  acc = row_reduce(acc);
+  acc = row_reduce_t<RL>(acc);
   const float nrm = __builtin_sqrtf(acc);
   if (act) {
-    for (int chunk = sub; chunk < nchunks; chunk += kRowLanes) {
+    for (int chunk = sub; chunk < nchunks; chunk += RL) {
       for (int e = 0; e < per; e++) {
         int j = chunk * per + e;
         if (j >= D) break;
@@ -51,8 +52,13 @@ __global__ __launch_bounds__(kWave) void normalise_kernel(const uint8_t* __restr
   }
 }
 hipError_t launch_normalise(const void* base, int dtype, int64_t N, int D, float* out, hipStream_t stream) {
-  const int64_t blocks = (N + kRowsPerPass - 1) / kRowsPerPass;
-  normalise_kernel<<<(unsigned)blocks, kWave, 0, stream>>>((const uint8_t*)base, dtype, N, D, out);
+  // the unit-length copy is float32: its row length decides how many lanes share a row
+  if ((size_t)D * 4 > (size_t)kRowLanes * 8 * 16) {
+    normalise_kernel<kWideRowLanes><<<(unsigned)N, kWave, 0, stream>>>((const uint8_t*)base, dtype, N, D, out);
+  } else {
+    const int64_t blocks = (N + kRowsPerPass - 1) / kRowsPerPass;
+    normalise_kernel<kRowLanes><<<(unsigned)blocks, kWave, 0, stream>>>((const uint8_t*)base, dtype, N, D, out);
+  }
   return hipGetLastError();
 }
 

@@ -10,8 +10,9 @@ namespace ggnn {
 typedef unsigned long long u64;
 
 constexpr int kWave = 64;
-constexpr int kRowLanes = 8;            // lanes that share one row (GGNN_ROW_LANES)
+constexpr int kRowLanes = 8;            // lanes that share one row of at most 1024 bytes (GGNN_ROW_LANES)
 constexpr int kRowsPerPass = kWave / kRowLanes;
+constexpr int kWideRowLanes = 64;       // longer rows take the whole wavefront (GGNN_WIDE_ROW_LANES)
 constexpr int kMaxLevels = 8;
 
 // What a kernel needs to know about the graph (passed by value).
@@ -277,14 +278,21 @@ __device__ inline void cache_transform(Cache& c, const int32_t* __restrict__ tab
 }
 
 // ---- distances ------------------------------------------------------------------------
-// Element types: 0 = float32 (4 per 16-byte chunk), 1 = uint8 (16 per chunk).
+// Row formats: 0 = float32 (4 per 16-byte chunk), 8 lanes per row; 1 = uint8 (16 per chunk), 8 lanes
+// per row; 2 = float32, the whole wavefront per row (rows longer than 1024 bytes).
 template <int DT> struct Elem;
-template <> struct Elem<0> { static constexpr int per_chunk = 4; };
-template <> struct Elem<1> { static constexpr int per_chunk = 16; };
+template <> struct Elem<0> { static constexpr int per_chunk = 4, lanes = kRowLanes; };
+template <> struct Elem<1> { static constexpr int per_chunk = 16, lanes = kRowLanes; };
+template <> struct Elem<2> { static constexpr int per_chunk = 4, lanes = kWideRowLanes; };
+// rows a wavefront takes per gather instruction, and gather instructions issued before the first use
+template <int DT, int PASSES> struct RowSched {
+  static constexpr int rows_per_pass = kWave / Elem<DT>::lanes;
+  static constexpr int passes = (Elem<DT>::lanes == kWave) ? 2 * PASSES : PASSES;
+};
 
 template <int DT>
 __device__ __forceinline__ void chunk_to_float(const uint4& v, float* out) {
-  if (DT == 0) {
+  if (DT != 1) {
     out[0] = __uint_as_float(v.x); out[1] = __uint_as_float(v.y);
     out[2] = __uint_as_float(v.z); out[3] = __uint_as_float(v.w);
   } else {
@@ -315,8 +323,19 @@ __device__ __forceinline__ float row_reduce(float acc) {
   acc = acc + dpp_move<0xB1, 0xF>(0.0f, acc);  // quad_perm [1,0,3,2]
   return acc;
 }
+// the same butterfly over LANES lanes (8 or 64): distances 32, 16, 8 go through the LDS crossbar
+// (ds_bpermute, no LDS memory), the last three are the DPP steps above
+template <int LANES>
+__device__ __forceinline__ float row_reduce_t(float acc) {
+  if (LANES == kWideRowLanes) {
+    acc = acc + __shfl_xor(acc, 32, kWave);
+    acc = acc + __shfl_xor(acc, 16, kWave);
+    acc = acc + __shfl_xor(acc, 8, kWave);
+  }
+  return row_reduce(acc);
+}
 
-// The query vector: lane (sub = lane & 7) keeps the elements of chunks sub, sub+8, ...
+// The query vector: lane (sub = lane mod row lanes) keeps the elements of chunks sub, sub + lanes, ...
 template <int DT, int NCH>
 struct QueryRegs {
   float v[NCH * Elem<DT>::per_chunk];
@@ -324,10 +343,11 @@ struct QueryRegs {
 
 template <int DT, int NCH>
 __device__ inline void load_query(QueryRegs<DT, NCH>& q, const uint8_t* row, int nchunks) {
-  const int sub = lane_id() & (kRowLanes - 1);
+  constexpr int RL = Elem<DT>::lanes;
+  const int sub = lane_id() & (RL - 1);
 #pragma unroll
   for (int c = 0; c < NCH; c++) {
-    int chunk = c * kRowLanes + sub;
+    int chunk = c * RL + sub;
     uint4 raw = make_uint4(0, 0, 0, 0);
     if (chunk < nchunks) raw = *(const uint4*)(row + (size_t)chunk * 16);
     chunk_to_float<DT>(raw, &q.v[c * Elem<DT>::per_chunk]);  // chunks past the row read as zeros
@@ -353,7 +373,7 @@ __device__ __forceinline__ float row_sum(const QueryRegs<DT, NCH>& q, const uint
       }
     }
   }
-  return row_reduce(acc);
+  return row_reduce_t<Elem<DT>::lanes>(acc);
 }
 // from the sum to the distance: METRIC 0: sqrt(sum), 1: max(0, 1 - sum)
 template <int METRIC>
@@ -391,24 +411,25 @@ __device__ inline void cache_fetch(Cache& c, const GraphDev& G, int layer, int32
     c.surv_row[r] = row;
   }
   wave_sync();
-  const int sub = lane & (kRowLanes - 1), grp = lane / kRowLanes;
-  for (int b0 = 0; b0 < ns; b0 += kRowsPerPass * PASSES) {
-    uint4 raw[PASSES][NCH];
+  constexpr int RL = Elem<DT>::lanes, RPP = RowSched<DT, PASSES>::rows_per_pass, NP = RowSched<DT, PASSES>::passes;
+  const int sub = lane & (RL - 1), grp = lane / RL;
+  for (int b0 = 0; b0 < ns; b0 += RPP * NP) {
+    uint4 raw[NP][NCH];
 #pragma unroll
-    for (int ps = 0; ps < PASSES; ps++) {
-      int r = b0 + ps * kRowsPerPass + grp;
+    for (int ps = 0; ps < NP; ps++) {
+      int r = b0 + ps * RPP + grp;
       bool act = r < ns;
       const uint8_t* ptr = G.rows + (size_t)(act ? c.surv_row[r] : 0) * (size_t)G.row_bytes;
 #pragma unroll
       for (int ch = 0; ch < NCH; ch++) {
-        int chunk = ch * kRowLanes + sub;
+        int chunk = ch * RL + sub;
         raw[ps][ch] = make_uint4(0, 0, 0, 0);
         if (act && chunk < G.nchunks) raw[ps][ch] = *(const uint4*)(ptr + (size_t)chunk * 16);
       }
     }
 #pragma unroll
-    for (int ps = 0; ps < PASSES; ps++) {
-      int r = b0 + ps * kRowsPerPass + grp;
+    for (int ps = 0; ps < NP; ps++) {
+      int r = b0 + ps * RPP + grp;
       float d = row_distance<DT, NCH, METRIC>(q, raw[ps]);
       if (r < ns && sub == 0) c.surv_d[r] = d;
     }

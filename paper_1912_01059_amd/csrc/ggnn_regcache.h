@@ -372,25 +372,26 @@ struct RegCacheT {
     }
     wave_sync();
     GGNN_TICK(4);  // compaction
-    const int sub = lane & (kRowLanes - 1), grp = lane / kRowLanes;
-    for (int b0 = 0; b0 < ns; b0 += kRowsPerPass * PASSES) {
-      uint4 raw[PASSES][NCH];
+    constexpr int RL = Elem<DT>::lanes, RPP = RowSched<DT, PASSES>::rows_per_pass, NP = RowSched<DT, PASSES>::passes;
+    const int sub = lane & (RL - 1), grp = lane / RL;
+    for (int b0 = 0; b0 < ns; b0 += RPP * NP) {
+      uint4 raw[NP][NCH];
 #pragma unroll
-      for (int ps = 0; ps < PASSES; ps++) {
-        const int r = b0 + ps * kRowsPerPass + grp;
+      for (int ps = 0; ps < NP; ps++) {
+        const int r = b0 + ps * RPP + grp;
         const bool act = r < ns;
         const uint8_t* ptr = G.rows + (size_t)(act ? surv_row[r] : 0) * (size_t)G.row_bytes;
 #pragma unroll
         for (int ch = 0; ch < NCH; ch++) {
-          const int chunk = ch * kRowLanes + sub;
+          const int chunk = ch * RL + sub;
           raw[ps][ch] = make_uint4(0, 0, 0, 0);
           if (act && chunk < G.nchunks) raw[ps][ch] = *(const uint4*)(ptr + (size_t)chunk * 16);
         }
       }
 #pragma unroll
-      for (int ps = 0; ps < PASSES; ps++) {
-        if (b0 + ps * kRowsPerPass < ns) {  // uniform: skip passes without rows
-          const int r = b0 + ps * kRowsPerPass + grp;
+      for (int ps = 0; ps < NP; ps++) {
+        if (b0 + ps * RPP < ns) {  // uniform: skip passes without rows
+          const int r = b0 + ps * RPP + grp;
           const float sum = row_sum<DT, NCH, METRIC>(q, raw[ps]);
           if (r < ns && sub == 0) surv_d[r] = sum;
         }

@@ -1,7 +1,8 @@
 // Search kernels: user query (Alg. 1 / Alg. 4, Sec. 4.4), construction query (Alg. 3 Merge,
 // Alg. 4) and the symmetric-linking query (Alg. 5, Sec. 4.2.1).  One wavefront per query.
 // The kernels are templates over the cache implementation (registers or LDS), the element type,
-// the number of 16-byte chunks a lane holds of a row, and the metric.
+// the row format (element type and lanes per row), the number of 16-byte chunks a lane holds of a
+// row, and the metric.
 #pragma once
 #include "ggnn_launch.h"
 #include "ggnn_regcache.h"
@@ -19,7 +20,7 @@ __device__ inline void normalise_query(QueryRegs<DT, NCH>& q) {
   float acc = 0.0f;
 #pragma unroll
   for (int i = 0; i < NCH * E; i++) acc = __builtin_fmaf(q.v[i], q.v[i], acc);
-  acc = row_reduce(acc);
+  acc = row_reduce_t<Elem<DT>::lanes>(acc);
   const float nrm = __builtin_sqrtf(acc);
   if (nrm > 0.0f) {
 #pragma unroll
@@ -169,10 +170,10 @@ __global__ __launch_bounds__(kWave) void sym_search_kernel(GraphDev G, int layer
   {
     // radius: distance from q_m to x, through the same summation order as every distance
     uint4 raw[NCH];
-    const int sub = lane & (kRowLanes - 1);
+    const int sub = lane & (Elem<DT>::lanes - 1);
 #pragma unroll
     for (int ch = 0; ch < NCH; ch++) {
-      const int chunk = ch * kRowLanes + sub;
+      const int chunk = ch * Elem<DT>::lanes + sub;
       raw[ch] = make_uint4(0, 0, 0, 0);
       if (chunk < G.nchunks) raw[ch] = *(const uint4*)(G.rows + (size_t)xrow * (size_t)G.row_bytes + (size_t)chunk * 16);
     }
@@ -198,26 +199,33 @@ __global__ __launch_bounds__(kWave) void sym_search_kernel(GraphDev G, int layer
 }
 
 // ---- dispatch over element type, chunks per lane and metric ---------------------------
-#define GGNN_DISPATCH(C, KERNEL, ...)                                                                   \
-  do {                                                                                                  \
-    const int need = (G.nchunks + kRowLanes - 1) / kRowLanes;                                           \
-    if (metric == 1) {                                                                                  \
-      if (need <= 1) KERNEL<C, 0, 1, 1><<<grid, kWave, lds, stream>>>(__VA_ARGS__);                     \
-      else if (need <= 3) KERNEL<C, 0, 3, 1><<<grid, kWave, lds, stream>>>(__VA_ARGS__);                \
-      else if (need <= 4) KERNEL<C, 0, 4, 1><<<grid, kWave, lds, stream>>>(__VA_ARGS__);                \
-      else if (need <= 8) KERNEL<C, 0, 8, 1><<<grid, kWave, lds, stream>>>(__VA_ARGS__);                \
-      else return hipErrorInvalidValue;                                                                 \
-    } else if (dtype == 0) {                                                                            \
-      if (need <= 1) KERNEL<C, 0, 1, 0><<<grid, kWave, lds, stream>>>(__VA_ARGS__);                     \
-      else if (need <= 3) KERNEL<C, 0, 3, 0><<<grid, kWave, lds, stream>>>(__VA_ARGS__);                \
-      else if (need <= 4) KERNEL<C, 0, 4, 0><<<grid, kWave, lds, stream>>>(__VA_ARGS__);                \
-      else if (need <= 8) KERNEL<C, 0, 8, 0><<<grid, kWave, lds, stream>>>(__VA_ARGS__);                \
-      else return hipErrorInvalidValue;                                                                 \
-    } else {                                                                                            \
-      if (need <= 1) KERNEL<C, 1, 1, 0><<<grid, kWave, lds, stream>>>(__VA_ARGS__);                     \
-      else if (need <= 2) KERNEL<C, 1, 2, 0><<<grid, kWave, lds, stream>>>(__VA_ARGS__);                \
-      else return hipErrorInvalidValue;                                                                 \
-    }                                                                                                   \
+// (rows of at most 1024 bytes: 8 lanes per row; longer float32 rows: the whole wavefront per row)
+#define GGNN_LAUNCH(C, KERNEL, DT, NCH, M, ...) KERNEL<C, DT, NCH, M><<<grid, kWave, lds, stream>>>(__VA_ARGS__)
+#define GGNN_DISPATCH(C, KERNEL, ...)                                                       \
+  do {                                                                                      \
+    const int need = (G.nchunks + kRowLanes - 1) / kRowLanes;                               \
+    const int wide = (G.nchunks + kWideRowLanes - 1) / kWideRowLanes;                       \
+    if (metric == 1) {                                                                      \
+      if (need <= 1) GGNN_LAUNCH(C, KERNEL, 0, 1, 1, __VA_ARGS__);                          \
+      else if (need <= 3) GGNN_LAUNCH(C, KERNEL, 0, 3, 1, __VA_ARGS__);                     \
+      else if (need <= 4) GGNN_LAUNCH(C, KERNEL, 0, 4, 1, __VA_ARGS__);                     \
+      else if (need <= 8) GGNN_LAUNCH(C, KERNEL, 0, 8, 1, __VA_ARGS__);                     \
+      else if (wide <= 2) GGNN_LAUNCH(C, KERNEL, 2, 2, 1, __VA_ARGS__);                     \
+      else if (wide <= 4) GGNN_LAUNCH(C, KERNEL, 2, 4, 1, __VA_ARGS__);                     \
+      else return hipErrorInvalidValue;                                                     \
+    } else if (dtype == 0) {                                                                \
+      if (need <= 1) GGNN_LAUNCH(C, KERNEL, 0, 1, 0, __VA_ARGS__);                          \
+      else if (need <= 3) GGNN_LAUNCH(C, KERNEL, 0, 3, 0, __VA_ARGS__);                     \
+      else if (need <= 4) GGNN_LAUNCH(C, KERNEL, 0, 4, 0, __VA_ARGS__);                     \
+      else if (need <= 8) GGNN_LAUNCH(C, KERNEL, 0, 8, 0, __VA_ARGS__);                     \
+      else if (wide <= 2) GGNN_LAUNCH(C, KERNEL, 2, 2, 0, __VA_ARGS__);                     \
+      else if (wide <= 4) GGNN_LAUNCH(C, KERNEL, 2, 4, 0, __VA_ARGS__);                     \
+      else return hipErrorInvalidValue;                                                     \
+    } else {                                                                                \
+      if (need <= 1) GGNN_LAUNCH(C, KERNEL, 1, 1, 0, __VA_ARGS__);                          \
+      else if (need <= 2) GGNN_LAUNCH(C, KERNEL, 1, 2, 0, __VA_ARGS__);                     \
+      else return hipErrorInvalidValue;                                                     \
+    }                                                                                       \
   } while (0)
 
 template <class C>

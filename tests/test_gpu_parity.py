@@ -275,6 +275,12 @@ def test_build_quality_and_recall(ggnn, R, sift10k, sift10k_gt):
     dict(N=3000, D=128, K=24, L=3, s=32, kind="u8"),            # uint8 rows
     dict(N=1200, D=96, K=25, L=3, s=32, kind="real"),           # odd K: k_nn = 12, k_sym = 13
     dict(N=890, D=64, K=24, L=2, s=64, kind="dups"),            # duplicated rows: distance ties, zero distances
+    dict(N=1500, D=960, K=24, L=2, s=32, kind="real"),          # rows above 1024 bytes: 64 lanes per row, ragged last chunk
+    dict(N=1200, D=320, K=24, L=3, s=32, kind="real"),          # 64 lanes per row, two chunks per lane, second one partly filled
+    dict(N=1000, D=300, K=24, L=2, s=32, kind="cosine"),        # cosine on rows above 1024 bytes
+    dict(N=900, D=1024, K=16, L=2, s=32, kind="int"),           # the longest float32 row
+    dict(N=1000, D=256, K=24, L=2, s=32, kind="u8"),            # the longest uint8 row
+    dict(N=1000, D=256, K=24, L=2, s=32, kind="real"),          # the longest float32 row with 8 lanes per row
 ])
 def test_full_build_matches_oracle_on_varied_shapes(ggnn, R, case):
     rng = np.random.default_rng(case["N"])

@@ -42,6 +42,13 @@ def test_argument_errors_are_reported_without_a_gpu():
     assert rc == -1
     rc = L.ggnn_merge(None, 0, 0)
     assert rc == -1
+    # row lengths: float32 up to 1024 elements, multiples of 16 bytes (a non-null dummy address is
+    # enough: arguments are checked before anything touches the device)
+    dummy = ctypes.c_void_p(4096)
+    assert L.ggnn_graph_create(dummy, 1000, 1028, 24, 3, 1, None, ctypes.byref(out)) == -1
+    assert b"too large" in L.ggnn_last_error()
+    assert L.ggnn_graph_create(dummy, 1000, 130, 24, 3, 1, None, ctypes.byref(out)) == -1
+    assert b"multiple of 16" in L.ggnn_last_error()
 
 
 def test_missing_library_fails_loudly(monkeypatch):

@@ -115,11 +115,13 @@ def test_distance_cosine():
         assert R.distance(qn, qn, metric=R.COSINE) <= 4 * D * 2.0 ** -24
 
 
-def test_distance_summation_tree_is_the_documented_one():
+@pytest.mark.parametrize("D,lanes", [(128, 8), (256, 8), (320, 64), (960, 64)])
+def test_distance_summation_tree_is_the_documented_one(D, lanes):
     """A value chosen so that summation order matters: the documented tree (chunks of 4
-    elements dealt to `lanes` accumulators, fma chains, butterfly) must be what is used."""
+    elements dealt to `lanes` accumulators, fma chains, butterfly) must be what is used; rows of at
+    most 1024 bytes take 8 accumulators, longer ones 64."""
     rng = np.random.default_rng(11)
-    D, lanes = 128, 8
+    assert R.row_lanes(D, 4) == lanes
     hits = 0
     for _ in range(20):
         q = (rng.standard_normal(D) * 10 ** rng.uniform(-3, 3, D)).astype(np.float32)
@@ -136,7 +138,7 @@ def test_distance_summation_tree_is_the_documented_one():
             part = [np.float32(part[l] + part[l ^ step]) for l in range(lanes)]
             step //= 2
         want = float(np.sqrt(part[0]))
-        assert R.distance(q, x, lanes=lanes) == want
+        assert R.distance(q, x) == want
         seq = np.float32(0)
         for j in range(D):
             seq = _fma32(q[j], q[j], seq)
