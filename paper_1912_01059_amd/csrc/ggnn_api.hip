@@ -120,6 +120,7 @@ GraphDev device_view(const ggnn_graph* g) {
   const int esize = (g->norm || g->dtype == GGNN_F32) ? 4 : 1;
   G.row_bytes = g->D * esize;
   G.nchunks = G.row_bytes / 16;
+  G.addr32 = ((uint64_t)g->N * (uint64_t)G.row_bytes < (1ull << 32)) ? 1 : 0;
   for (int l = 0; l < g->L; l++) {
     G.n[l] = g->n[l];
     G.edges[l] = g->edges[l];

@@ -21,6 +21,7 @@ struct GraphDev {
   int64_t N;
   int32_t D, K, L, s, g;
   int32_t row_bytes, nchunks;  // bytes per row, 16-byte chunks per row
+  int32_t addr32;              // 1: every byte offset into rows fits 32 bits (N * row_bytes < 2^32)
   int64_t n[kMaxLevels];
   const int32_t* edges[kMaxLevels];
   const int32_t* to_lower[kMaxLevels];
@@ -384,6 +385,45 @@ __device__ __forceinline__ float finish_distance(float sum) {
 template <int DT, int NCH, int METRIC>
 __device__ __forceinline__ float row_distance(const QueryRegs<DT, NCH>& q, const uint4 (&raw)[NCH]) {
   return finish_distance<METRIC>(row_sum<DT, NCH, METRIC>(q, raw));
+}
+
+// Requests the rows of one batch of survivors (8 lanes x 16 bytes per row, or the whole wavefront per
+// long row), every load issued before the first use.  When all byte offsets fit 32 bits the address is
+// the uniform base plus a 32-bit lane offset plus a constant per chunk.  FULL: every lane owns NCH
+// chunks of the row (no ragged tail), so the loads of a row share one predicate.
+template <int DT, int NCH, int NP, bool FULL, bool A32>
+__device__ __forceinline__ void gather_rows_t(const GraphDev& G, const int32_t* surv_row, int b0, int ns,
+                                              uint4 (&raw)[NP][NCH]) {
+  constexpr int RL = Elem<DT>::lanes, RPP = kWave / RL;
+  const int lane = lane_id(), sub = lane & (RL - 1), grp = lane / RL;
+#pragma unroll
+  for (int ps = 0; ps < NP; ps++) {
+    const int r = b0 + ps * RPP + grp;
+    const bool act = r < ns;
+    const uint32_t row = (uint32_t)(act ? surv_row[r] : 0);
+    const uint8_t* ptr;
+    if (A32) ptr = G.rows + (row * (uint32_t)G.row_bytes + (uint32_t)sub * 16u);
+    else ptr = G.rows + ((size_t)row * (size_t)G.row_bytes + (size_t)sub * 16u);
+#pragma unroll
+    for (int ch = 0; ch < NCH; ch++) raw[ps][ch] = make_uint4(0, 0, 0, 0);
+    if (act) {
+#pragma unroll
+      for (int ch = 0; ch < NCH; ch++)
+        if (FULL || ch * RL + sub < G.nchunks) raw[ps][ch] = *(const uint4*)(ptr + ch * RL * 16);
+    }
+  }
+}
+template <int DT, int NCH, int NP>
+__device__ __forceinline__ void gather_rows(const GraphDev& G, const int32_t* surv_row, int b0, int ns,
+                                            uint4 (&raw)[NP][NCH]) {
+  const bool full = G.nchunks == NCH * Elem<DT>::lanes;
+  if (G.addr32) {
+    if (full) gather_rows_t<DT, NCH, NP, true, true>(G, surv_row, b0, ns, raw);
+    else gather_rows_t<DT, NCH, NP, false, true>(G, surv_row, b0, ns, raw);
+  } else {
+    if (full) gather_rows_t<DT, NCH, NP, true, false>(G, surv_row, b0, ns, raw);
+    else gather_rows_t<DT, NCH, NP, false, false>(G, surv_row, b0, ns, raw);
+  }
 }
 
 // Alg. 2 Fetch.  Lane j holds proposal p (or -1).  Known points are dropped against the

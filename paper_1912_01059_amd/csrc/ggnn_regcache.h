@@ -116,12 +116,6 @@ struct RegCacheT {
     for (int i = lane_id(); i < kListedBuckets / 32; i += kWave) listed_bits[i] = 0;
     wave_sync();
   }
-  __device__ __forceinline__ void listed_add(int32_t id) {  // uniform call
-    if (lane_id() == 0) {
-      const uint32_t h = listed_bucket(id);
-      atomicOr(&listed_bits[h >> 5], 1u << (h & 31));
-    }
-  }
   __device__ __forceinline__ bool maybe_listed(int32_t id) const {
     const uint32_t h = listed_bucket(id);
     return (listed_bits[h >> 5] >> (h & 31)) & 1u;
@@ -196,7 +190,7 @@ struct RegCacheT {
     const int pos = __popcll(__ballot(lt));
     const u64 up = wave_shift_up(L, key);
     L = lt ? L : (lane == pos ? key : up);
-    if (lane >= cap) L = kEmptyKey;
+    if (cap < kWave && lane >= cap) L = kEmptyKey;
     if (pos < cap && n < cap) n++;
   }
   // the same for best, which may span several registers: what leaves lane 63 of one register
@@ -223,18 +217,6 @@ struct RegCacheT {
     }
     if (nb < B) nb++;
   }
-  // Alg. 2 Push (the key is known not to be in either list).  Most accepted candidates lie
-  // between the k-th best distance and the threshold: they enter prioq only, so best (and the
-  // bounds derived from it) is touched only when the key really belongs there.
-  __device__ void push(u64 key) {
-    if (nb < B || key < last_best) {
-      best_insert(key);
-      refresh_bounds();
-    }
-    list_insert(pq, np, P, key);
-    listed_add(key_id(key));
-  }
-
   // Alg. 2 Pop, first half: take the head off prioq (or -1 when the search on this layer ends).
   // The caller completes the pop with mark_visited(id) once the adjacency load is under way.
   __device__ int32_t pop_head() {
@@ -376,18 +358,7 @@ struct RegCacheT {
     const int sub = lane & (RL - 1), grp = lane / RL;
     for (int b0 = 0; b0 < ns; b0 += RPP * NP) {
       uint4 raw[NP][NCH];
-#pragma unroll
-      for (int ps = 0; ps < NP; ps++) {
-        const int r = b0 + ps * RPP + grp;
-        const bool act = r < ns;
-        const uint8_t* ptr = G.rows + (size_t)(act ? surv_row[r] : 0) * (size_t)G.row_bytes;
-#pragma unroll
-        for (int ch = 0; ch < NCH; ch++) {
-          const int chunk = ch * RL + sub;
-          raw[ps][ch] = make_uint4(0, 0, 0, 0);
-          if (act && chunk < G.nchunks) raw[ps][ch] = *(const uint4*)(ptr + (size_t)chunk * 16);
-        }
-      }
+      gather_rows<DT, NCH, NP>(G, surv_row, b0, ns, raw);
 #pragma unroll
       for (int ps = 0; ps < NP; ps++) {
         if (b0 + ps * RPP < ns) {  // uniform: skip passes without rows
@@ -399,30 +370,49 @@ struct RegCacheT {
     }
     wave_sync();
     GGNN_TICK(5);  // gather + distances
-    // Survivors are pushed in list order with the threshold re-evaluated after every push.  The
-    // threshold only shrinks, so whoever fails the threshold as it stands now fails later too:
-    // only the others go through the sequential loop.
+    // Alg. 2 Push, for the survivors in list order with the threshold re-evaluated after every push.
+    // The threshold only shrinks, and only when a key enters best: the candidates that may enter
+    // best are taken one by one, in order, and every lane notes the threshold in force when its own
+    // candidate is reached; all others are decided at once against that threshold.
     const bool mine = lane < ns;
     const float d = mine ? finish_distance<METRIC>(surv_d[lane]) : INFINITY;  // one sqrt for the whole fetch
     const int32_t id = mine ? surv_id[lane] : -1;
-    u64 todo = __ballot(mine && d <= thr() && d <= radius);
-    u64 accepted = 0;
-    while (todo) {
-      const int r = __builtin_ctzll(todo);
-      todo &= todo - 1;
-      const float dr = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(d), r));
+    const u64 key = make_key(d, id);
+    const bool in = mine && d <= thr() && d <= radius;
+    const u64 last_best0 = (nb < B) ? kEmptyKey : last_best;
+    float mythr = thr();
+    u64 first = __ballot(in && key < last_best0);
+    while (first) {
+      const int r = __builtin_ctzll(first);
+      first &= first - 1;
+      const u64 kr = read_lane_u64(key, r);
 #ifdef GGNN_PHASE_TIMING
       ph[8]++;
-      if (dr <= thr()) ph[9]++;
-      ph[10] += (uint32_t)ns;
 #endif
-      if (dr <= thr()) {
-        push(make_key(dr, __builtin_amdgcn_readlane(id, r)));
-        accepted |= 1ull << r;
+      if (key_d(kr) <= thr() && (nb < B || kr < last_best)) {
+        best_insert(kr);
+        refresh_bounds();
+        mythr = (lane > r) ? thr() : mythr;
       }
     }
-    GGNN_TICK(6);  // acceptance loop and pushes
-    insert_rejected(mine && !((accepted >> lane) & 1), id);
+    const bool ok = in && d <= mythr;  // accepted
+    // prioq: a key beyond the last entry of a full prioq would fall off at once
+    const u64 pq_last = (np < P) ? kEmptyKey : read_lane_u64(pq, P - 1);
+    u64 ins = __ballot(ok && key < pq_last);
+    while (ins) {
+      const int r = __builtin_ctzll(ins);
+      ins &= ins - 1;
+#ifdef GGNN_PHASE_TIMING
+      ph[9]++;
+#endif
+      list_insert(pq, np, P, read_lane_u64(key, r));
+    }
+    if (ok && (key < pq_last || key < last_best0)) {  // whatever entered a list is marked in the bit map
+      const uint32_t h = listed_bucket(id);
+      atomicOr(&listed_bits[h >> 5], 1u << (h & 31));
+    }
+    GGNN_TICK(6);  // acceptance and pushes
+    insert_rejected(mine && !ok, id);
     GGNN_TICK(7);  // rejected filter
   }
 
