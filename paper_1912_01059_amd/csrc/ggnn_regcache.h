@@ -334,6 +334,9 @@ struct RegCacheT {
       const int j = __builtin_ctzll(cand);
       cand &= cand - 1;
       const int32_t pid = __builtin_amdgcn_readlane(p, j);
+#ifdef GGNN_PHASE_TIMING
+      ph[11]++;
+#endif
       bool hit = key_id(pq) == pid;
 #pragma unroll
       for (int e = 0; e < NB; e++) hit = hit || key_id(best[e]) == pid;
@@ -347,6 +350,9 @@ struct RegCacheT {
     evals += ns + __popcll(__ballot(seen_rejected));
     if (ns == 0) return;
     gathers += ns;
+#ifdef GGNN_PHASE_TIMING
+    ph[10] += (uint32_t)ns;
+#endif
     if (alive) {
       const int r = __popcll(mask & ((1ull << lane) - 1));
       surv_id[r] = p;
@@ -398,14 +404,41 @@ struct RegCacheT {
     const bool ok = in && d <= mythr;  // accepted
     // prioq: a key beyond the last entry of a full prioq would fall off at once
     const u64 pq_last = (np < P) ? kEmptyKey : read_lane_u64(pq, P - 1);
-    u64 ins = __ballot(ok && key < pq_last);
-    while (ins) {
-      const int r = __builtin_ctzll(ins);
-      ins &= ins - 1;
+    const bool goes_in = ok && key < pq_last;
+    u64 ins = __ballot(goes_in);
+    const int m = __popcll(ins);
 #ifdef GGNN_PHASE_TIMING
-      ph[9]++;
+    ph[9] += (uint32_t)m;
 #endif
-      list_insert(pq, np, P, read_lane_u64(key, r));
+    if (m <= 2) {
+      while (ins) {
+        const int r = __builtin_ctzll(ins);
+        ins &= ins - 1;
+        list_insert(pq, np, P, read_lane_u64(key, r));
+      }
+    } else {
+      // Several keys at once: every prioq entry counts the new keys below it (it moves up by that
+      // many places), every new key counts the entries and the other new keys below it; both
+      // then go to their places through LDS (the survivor arrays are free by now).  The result is
+      // that of inserting one by one: the P smallest of the union, in order.
+      int up = 0, rank = 0;
+      while (ins) {
+        const int r = __builtin_ctzll(ins);
+        ins &= ins - 1;
+        const u64 kr = read_lane_u64(key, r);
+        const bool lt = pq < kr;
+        const int below = __popcll(__ballot(lt));
+        up += lt ? 0 : 1;
+        rank += (kr < key) ? 1 : 0;
+        if (lane == r) rank += below;
+      }
+      u64* out = (u64*)surv_id;  // 64 keys: surv_id and surv_row
+      if (lane < np && lane + up < P) out[lane + up] = pq;
+      if (goes_in && rank < P) out[rank] = key;
+      wave_sync();
+      np = (np + m < P) ? np + m : P;
+      pq = (lane < np) ? out[lane] : kEmptyKey;
+      wave_sync();
     }
     if (ok && (key < pq_last || key < last_best0)) {  // whatever entered a list is marked in the bit map
       const uint32_t h = listed_bucket(id);

@@ -14,6 +14,14 @@ namespace ggnn {
 #endif
 constexpr int kPasses = GGNN_PASSES;  // 8 rows per pass: up to 8*kPasses rows in flight per wavefront
 
+// Wavefronts per SIMD the register allocation of merge_kernel aims at: with rows of up to 512 bytes six
+// fit at the price of two spilled registers outside the loop, and the construction is faster for it
+// (the user-query and sym kernels would spill inside the loop and are left alone).
+template <int DT, int NCH>
+struct MergeWavesPerSimd {
+  static constexpr int value = (Elem<DT>::lanes == kRowLanes && NCH <= 4) ? 6 : 1;
+};
+
 template <int DT, int NCH>
 __device__ inline void normalise_query(QueryRegs<DT, NCH>& q) {
   constexpr int E = Elem<DT>::per_chunk;
@@ -88,7 +96,7 @@ __global__ __launch_bounds__(kWave) void query_kernel(GraphDev G, const uint8_t*
 }
 
 template <class C, int DT, int NCH, int METRIC>
-__global__ __launch_bounds__(kWave) void merge_kernel(GraphDev G, int l_top, int l_m, SearchParams sp,
+__global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(MergeWavesPerSimd<DT, NCH>::value))) void merge_kernel(GraphDev G, int l_top, int l_m, SearchParams sp,
                                                       int32_t* __restrict__ out_rows, float* __restrict__ dnn1,
                                                       unsigned long long* __restrict__ work) {
   extern __shared__ __align__(16) unsigned char lds[];
