@@ -387,42 +387,55 @@ __device__ __forceinline__ float row_distance(const QueryRegs<DT, NCH>& q, const
   return finish_distance<METRIC>(row_sum<DT, NCH, METRIC>(q, raw));
 }
 
-// Requests the rows of one batch of survivors (8 lanes x 16 bytes per row, or the whole wavefront per
-// long row), every load issued before the first use.  When all byte offsets fit 32 bits the address is
-// the uniform base plus a 32-bit lane offset plus a constant per chunk.  FULL: every lane owns NCH
-// chunks of the row (no ragged tail), so the loads of a row share one predicate.
-template <int DT, int NCH, int NP, bool FULL, bool A32>
-__device__ __forceinline__ void gather_rows_t(const GraphDev& G, const int32_t* surv_row, int b0, int ns,
-                                              uint4 (&raw)[NP][NCH]) {
+// One batch of survivors (rows b0 .. of surv_row): requests the rows (8 lanes x 16 bytes per row, or
+// the whole wavefront per long row), every load issued before the first use, then leaves the sum of
+// every row in surv_sum.  A pass takes kWave / lanes rows.  Lanes without a row read row 0 (their sums
+// are never stored), so nothing is spent on clearing registers or masking loads; the arithmetic of a
+// pass without rows is skipped.  When all byte offsets fit 32 bits the address is the uniform base
+// plus a 32-bit lane offset plus a constant per chunk.  FULL: every lane owns NCH chunks of the row
+// (no ragged tail).
+template <int DT, int NCH, int METRIC, int NP, bool FULL, bool A32>
+__device__ __forceinline__ void gather_sum_t(const GraphDev& G, const QueryRegs<DT, NCH>& q, const int32_t* surv_row,
+                                             float* surv_sum, int b0, int ns) {
   constexpr int RL = Elem<DT>::lanes, RPP = kWave / RL;
   const int lane = lane_id(), sub = lane & (RL - 1), grp = lane / RL;
+  uint4 raw[NP][NCH];
 #pragma unroll
   for (int ps = 0; ps < NP; ps++) {
     const int r = b0 + ps * RPP + grp;
-    const bool act = r < ns;
-    const uint32_t row = (uint32_t)(act ? surv_row[r] : 0);
+    const uint32_t row = (r < ns) ? (uint32_t)surv_row[r] : 0u;
     const uint8_t* ptr;
     if (A32) ptr = G.rows + (row * (uint32_t)G.row_bytes + (uint32_t)sub * 16u);
-    else ptr = G.rows + ((size_t)row * (size_t)G.row_bytes + (size_t)sub * 16u);
+    else ptr = G.rows + ((uint64_t)row * (uint32_t)G.row_bytes + (uint32_t)sub * 16u);
 #pragma unroll
-    for (int ch = 0; ch < NCH; ch++) raw[ps][ch] = make_uint4(0, 0, 0, 0);
-    if (act) {
+    for (int ch = 0; ch < NCH; ch++) {
+      if (FULL) {
+        raw[ps][ch] = *(const uint4*)(ptr + ch * RL * 16);
+      } else {
+        raw[ps][ch] = make_uint4(0, 0, 0, 0);  // chunks past the row read as zeros
+        if (ch * RL + sub < G.nchunks) raw[ps][ch] = *(const uint4*)(ptr + ch * RL * 16);
+      }
+    }
+  }
 #pragma unroll
-      for (int ch = 0; ch < NCH; ch++)
-        if (FULL || ch * RL + sub < G.nchunks) raw[ps][ch] = *(const uint4*)(ptr + ch * RL * 16);
+  for (int ps = 0; ps < NP; ps++) {
+    if (b0 + ps * RPP < ns) {  // uniform
+      const int r = b0 + ps * RPP + grp;
+      const float sum = row_sum<DT, NCH, METRIC>(q, raw[ps]);
+      if (r < ns && sub == 0) surv_sum[r] = sum;
     }
   }
 }
-template <int DT, int NCH, int NP>
-__device__ __forceinline__ void gather_rows(const GraphDev& G, const int32_t* surv_row, int b0, int ns,
-                                            uint4 (&raw)[NP][NCH]) {
+template <int DT, int NCH, int METRIC, int NP>
+__device__ __forceinline__ void gather_sum(const GraphDev& G, const QueryRegs<DT, NCH>& q, const int32_t* surv_row,
+                                           float* surv_sum, int b0, int ns) {
   const bool full = G.nchunks == NCH * Elem<DT>::lanes;
   if (G.addr32) {
-    if (full) gather_rows_t<DT, NCH, NP, true, true>(G, surv_row, b0, ns, raw);
-    else gather_rows_t<DT, NCH, NP, false, true>(G, surv_row, b0, ns, raw);
+    if (full) gather_sum_t<DT, NCH, METRIC, NP, true, true>(G, q, surv_row, surv_sum, b0, ns);
+    else gather_sum_t<DT, NCH, METRIC, NP, false, true>(G, q, surv_row, surv_sum, b0, ns);
   } else {
-    if (full) gather_rows_t<DT, NCH, NP, true, false>(G, surv_row, b0, ns, raw);
-    else gather_rows_t<DT, NCH, NP, false, false>(G, surv_row, b0, ns, raw);
+    if (full) gather_sum_t<DT, NCH, METRIC, NP, true, false>(G, q, surv_row, surv_sum, b0, ns);
+    else gather_sum_t<DT, NCH, METRIC, NP, false, false>(G, q, surv_row, surv_sum, b0, ns);
   }
 }
 

@@ -360,20 +360,8 @@ struct RegCacheT {
     }
     wave_sync();
     GGNN_TICK(4);  // compaction
-    constexpr int RL = Elem<DT>::lanes, RPP = RowSched<DT, PASSES>::rows_per_pass, NP = RowSched<DT, PASSES>::passes;
-    const int sub = lane & (RL - 1), grp = lane / RL;
-    for (int b0 = 0; b0 < ns; b0 += RPP * NP) {
-      uint4 raw[NP][NCH];
-      gather_rows<DT, NCH, NP>(G, surv_row, b0, ns, raw);
-#pragma unroll
-      for (int ps = 0; ps < NP; ps++) {
-        if (b0 + ps * RPP < ns) {  // uniform: skip passes without rows
-          const int r = b0 + ps * RPP + grp;
-          const float sum = row_sum<DT, NCH, METRIC>(q, raw[ps]);
-          if (r < ns && sub == 0) surv_d[r] = sum;
-        }
-      }
-    }
+    constexpr int RPP = RowSched<DT, PASSES>::rows_per_pass, NP = RowSched<DT, PASSES>::passes;
+    for (int b0 = 0; b0 < ns; b0 += RPP * NP) gather_sum<DT, NCH, METRIC, NP>(G, q, surv_row, surv_d, b0, ns);
     wave_sync();
     GGNN_TICK(5);  // gather + distances
     // Alg. 2 Push, for the survivors in list order with the threshold re-evaluated after every push.
