@@ -74,7 +74,8 @@ struct RegCacheT {
 
   static constexpr int kListedBuckets = 8192;
   // Hash slots: room for every visited id plus at least 128 rejected ids at a load of one half;
-  // 1024 slots (4 KB) when that suffices, so that five wavefronts per SIMD fit into the LDS.
+  // 1024 slots (4 KB) when that suffices, so that six wavefronts per SIMD fit into the LDS (fewer slots
+  // remember fewer rejected points and cost more than they save).
   __host__ __device__ static int hash_slots(int max_iter) {
     int h = 1024;
     while (h < 2 * max_iter + 256) h <<= 1;

@@ -14,11 +14,12 @@ namespace ggnn {
 #endif
 constexpr int kPasses = GGNN_PASSES;  // 8 rows per pass: up to 8*kPasses rows in flight per wavefront
 
-// Wavefronts per SIMD the register allocation of merge_kernel aims at: with rows of up to 512 bytes six
-// fit at the price of two spilled registers outside the loop, and the construction is faster for it
-// (the user-query and sym kernels would spill inside the loop and are left alone).
+// Wavefronts per SIMD the register allocation of query_kernel and merge_kernel aims at: with rows of up
+// to 512 bytes six fit (80 registers; the user-query kernel then spills a few registers around
+// Transform, once per layer, not inside the search loop), and both are faster for the added residency.
+// The sym kernel would spill inside its loop and is left alone.
 template <int DT, int NCH>
-struct MergeWavesPerSimd {
+struct SearchWavesPerSimd {
   static constexpr int value = (Elem<DT>::lanes == kRowLanes && NCH <= 4) ? 6 : 1;
 };
 
@@ -51,7 +52,7 @@ __device__ inline void descend(C& c, const GraphDev& G, int layer, const QueryRe
 }
 
 template <class C, int DT, int NCH, int METRIC>
-__global__ __launch_bounds__(kWave) void query_kernel(GraphDev G, const uint8_t* __restrict__ queries, int k,
+__global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(SearchWavesPerSimd<DT, NCH>::value))) void query_kernel(GraphDev G, const uint8_t* __restrict__ queries, int k,
                                                       SearchParams sp, int every_layer, int32_t* __restrict__ ids,
                                                       float* __restrict__ dists, uint32_t* __restrict__ counters) {
   extern __shared__ __align__(16) unsigned char lds[];
@@ -96,7 +97,7 @@ __global__ __launch_bounds__(kWave) void query_kernel(GraphDev G, const uint8_t*
 }
 
 template <class C, int DT, int NCH, int METRIC>
-__global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(MergeWavesPerSimd<DT, NCH>::value))) void merge_kernel(GraphDev G, int l_top, int l_m, SearchParams sp,
+__global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(SearchWavesPerSimd<DT, NCH>::value))) void merge_kernel(GraphDev G, int l_top, int l_m, SearchParams sp,
                                                       int32_t* __restrict__ out_rows, float* __restrict__ dnn1,
                                                       unsigned long long* __restrict__ work) {
   extern __shared__ __align__(16) unsigned char lds[];
