@@ -23,7 +23,9 @@
  *    acc = fma(t, t, acc) over its chunks in ascending order, and the R lanes are combined
  *    by a butterfly (distance R/2, ..., 2, 1).  R = GGNN_ROW_LANES for rows of at most 1024
  *    bytes (for cosine: of the float32 unit-length copy), GGNN_WIDE_ROW_LANES for longer rows.
- *  - Row lengths: a multiple of 16 bytes; float32 D <= 1024, uint8 D <= 256.
+ *  - Row lengths: a multiple of 16 bytes; float32 D <= 1024, uint8 D <= 256.  The vector array (for
+ *    cosine: its float32 unit-length copy) must be smaller than 4 GiB: rows are addressed with 32-bit
+ *    byte offsets (GGNN_ERR_LIMIT otherwise).
  */
 #ifndef GGNN_H
 #define GGNN_H
@@ -47,7 +49,7 @@ typedef enum {
   GGNN_ERR_INVALID = -1, /* bad argument (null pointer, size out of range, ...) */
   GGNN_ERR_MEMORY = -2,  /* device or host allocation failed                    */
   GGNN_ERR_HIP = -3,     /* a HIP runtime call or kernel launch failed          */
-  GGNN_ERR_LIMIT = -4    /* a capacity exceeds what one workgroup's LDS holds   */
+  GGNN_ERR_LIMIT = -4    /* a capacity exceeds what one workgroup's LDS holds, or the vector array is too large */
 } ggnn_status;
 
 /* Construction parameters (appendix "Choosing Search-Graph Construction Parameters").

@@ -120,7 +120,6 @@ GraphDev device_view(const ggnn_graph* g) {
   const int esize = (g->norm || g->dtype == GGNN_F32) ? 4 : 1;
   G.row_bytes = g->D * esize;
   G.nchunks = G.row_bytes / 16;
-  G.addr32 = ((uint64_t)g->N * (uint64_t)G.row_bytes < (1ull << 32)) ? 1 : 0;
   for (int l = 0; l < g->L; l++) {
     G.n[l] = g->n[l];
     G.edges[l] = g->edges[l];
@@ -295,6 +294,11 @@ int ggnn_graph_create(const void* base_dev, int64_t N, int32_t D, int32_t K, int
   if ((dtype == GGNN_F32 && D > 1024) || (dtype == GGNN_U8 && D > 256))
     return fail(GGNN_ERR_INVALID, "D = %d too large (float32: <= 1024, uint8: <= 256)", D);
   if (((uintptr_t)base_dev) % 16 != 0) return fail(GGNN_ERR_INVALID, "base_dev is not 16-byte aligned");
+  // the search kernels address rows with 32-bit byte offsets (for cosine: rows of the float32 copy)
+  const uint64_t array_bytes = (uint64_t)N * (uint64_t)D * (uint64_t)(metric == GGNN_COSINE ? 4 : esize);
+  if (array_bytes >= (1ull << 32))
+    return fail(GGNN_ERR_LIMIT, "the vector array holds %llu bytes; this build accepts arrays below 4 GiB",
+                (unsigned long long)array_bytes);
 
   ggnn_graph* g = new (std::nothrow) ggnn_graph();
   if (!g) return fail(GGNN_ERR_MEMORY, "host allocation failed");

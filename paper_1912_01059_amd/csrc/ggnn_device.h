@@ -21,7 +21,6 @@ struct GraphDev {
   int64_t N;
   int32_t D, K, L, s, g;
   int32_t row_bytes, nchunks;  // bytes per row, 16-byte chunks per row
-  int32_t addr32;              // 1: every byte offset into rows fits 32 bits (N * row_bytes < 2^32)
   int64_t n[kMaxLevels];
   const int32_t* edges[kMaxLevels];
   const int32_t* to_lower[kMaxLevels];
@@ -391,10 +390,10 @@ __device__ __forceinline__ float row_distance(const QueryRegs<DT, NCH>& q, const
 // the whole wavefront per long row), every load issued before the first use, then leaves the sum of
 // every row in surv_sum.  A pass takes kWave / lanes rows.  Lanes without a row read row 0 (their sums
 // are never stored), so nothing is spent on clearing registers or masking loads; the arithmetic of a
-// pass without rows is skipped.  When all byte offsets fit 32 bits the address is the uniform base
-// plus a 32-bit lane offset plus a constant per chunk.  FULL: every lane owns NCH chunks of the row
-// (no ragged tail).
-template <int DT, int NCH, int METRIC, int NP, bool FULL, bool A32>
+// pass without rows is skipped.  All byte offsets fit 32 bits (the library accepts no larger array): the
+// address is the uniform base plus a 32-bit lane offset plus a constant per chunk.  FULL: every lane
+// owns NCH chunks of the row (no ragged tail).
+template <int DT, int NCH, int METRIC, int NP, bool FULL>
 __device__ __forceinline__ void gather_sum_t(const GraphDev& G, const QueryRegs<DT, NCH>& q, const int32_t* surv_row,
                                              float* surv_sum, int b0, int ns) {
   constexpr int RL = Elem<DT>::lanes, RPP = kWave / RL;
@@ -404,9 +403,7 @@ __device__ __forceinline__ void gather_sum_t(const GraphDev& G, const QueryRegs<
   for (int ps = 0; ps < NP; ps++) {
     const int r = b0 + ps * RPP + grp;
     const uint32_t row = (r < ns) ? (uint32_t)surv_row[r] : 0u;
-    const uint8_t* ptr;
-    if (A32) ptr = G.rows + (row * (uint32_t)G.row_bytes + (uint32_t)sub * 16u);
-    else ptr = G.rows + ((uint64_t)row * (uint32_t)G.row_bytes + (uint32_t)sub * 16u);
+    const uint8_t* ptr = G.rows + (row * (uint32_t)G.row_bytes + (uint32_t)sub * 16u);
 #pragma unroll
     for (int ch = 0; ch < NCH; ch++) {
       if (FULL) {
@@ -430,13 +427,8 @@ template <int DT, int NCH, int METRIC, int NP>
 __device__ __forceinline__ void gather_sum(const GraphDev& G, const QueryRegs<DT, NCH>& q, const int32_t* surv_row,
                                            float* surv_sum, int b0, int ns) {
   const bool full = G.nchunks == NCH * Elem<DT>::lanes;
-  if (G.addr32) {
-    if (full) gather_sum_t<DT, NCH, METRIC, NP, true, true>(G, q, surv_row, surv_sum, b0, ns);
-    else gather_sum_t<DT, NCH, METRIC, NP, false, true>(G, q, surv_row, surv_sum, b0, ns);
-  } else {
-    if (full) gather_sum_t<DT, NCH, METRIC, NP, true, false>(G, q, surv_row, surv_sum, b0, ns);
-    else gather_sum_t<DT, NCH, METRIC, NP, false, false>(G, q, surv_row, surv_sum, b0, ns);
-  }
+  if (full) gather_sum_t<DT, NCH, METRIC, NP, true>(G, q, surv_row, surv_sum, b0, ns);
+  else gather_sum_t<DT, NCH, METRIC, NP, false>(G, q, surv_row, surv_sum, b0, ns);
 }
 
 // Alg. 2 Fetch.  Lane j holds proposal p (or -1).  Known points are dropped against the
