@@ -52,9 +52,9 @@ def main():
     ap.add_argument("--workload", default="sift1m")
     ap.add_argument("--n", type=int, default=None, help="override the number of base points (debugging)")
     ap.add_argument("--levels", type=int, default=3)
-    ap.add_argument("--slack", type=float, default=0.05, help="tau_q of the timed operating point")
+    ap.add_argument("--slack", type=float, default=0.048, help="tau_q of the timed operating point")
     ap.add_argument("--beam", type=int, default=10)
-    ap.add_argument("--visited-cap", type=int, default=64, help="visited capacity = iteration limit per layer")
+    ap.add_argument("--visited-cap", type=int, default=48, help="visited capacity = iteration limit per layer")
     ap.add_argument("--pq-cap", type=int, default=64)
     ap.add_argument("--large-batch", type=int, default=100_000, help="also time a batch of this many queries (0 = skip)")
     ap.add_argument("--build-iter", type=int, default=192,
@@ -120,8 +120,8 @@ def main():
     curve = []
     if args.sweep:
         sweep = [dict(beam=10, slack=sl, visited_cap=v, pq_cap=64)
-                 for (sl, v) in [(0.02, 64), (0.03, 64), (0.04, 64), (0.05, 64), (0.065, 96), (0.08, 128), (0.1, 192),
-                                 (0.15, 384), (0.2, 512), (0.3, 1024)]]
+                 for (sl, v) in [(0.02, 40), (0.03, 40), (0.04, 48), (0.044, 48), (0.048, 48), (0.05, 56), (0.05, 64),
+                                 (0.065, 96), (0.08, 128), (0.1, 192), (0.15, 384), (0.2, 512), (0.3, 1024)]]
         for op in sweep:
             okw = dict(pq_cap=op["pq_cap"], visited_cap=op["visited_cap"], every_layer=True)
             _, _, c = graph.query(queries, k, op["beam"], op["slack"], counters=True, out=(ids, dists), **okw)
