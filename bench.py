@@ -114,7 +114,7 @@ def main():
                       "frac": round(merge_bytes / (phases["merge_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                       "pops": int(phases["merge_pops"]), "rows_gathered": int(phases["merge_rows"]),
                       "note": "algorithmic bytes: rows served by the L2 count too, so the rate can exceed the HBM "
-                              "peak; the bottom-layer merge fetches 5.6 TB/s from HBM (profiles/query_kernel_sift1m_pmc.txt)"}
+                              "peak; HBM-side rates measured with counters are in profiles/"}
 
     gt_ids, gt_d = ground_truth(torch, base, queries, k, cosine=(metric == ggnn.COSINE))
     rel = 0.0 if cfg["kind"] == "gmm" else 2e-5  # integer-valued rows have exact float32 distances
