@@ -22,11 +22,11 @@ def workload():
     base, queries, cfg = ggnn_inputs.make("sift1m")
     b = torch.from_numpy(base).cuda()
     q = torch.from_numpy(queries).cuda()
-    g = ggnn.build(b, cfg["K"], 3, seed=42)
+    g = ggnn.build(b, cfg["K"], 3, seed=42, visited_cap=192, max_iter=192)  # bench.py's construction
     return ggnn, base, queries, cfg, b, q, g
 
 
-OP = dict(k=10, beam=10, slack=0.05, visited_cap=64, pq_cap=64, every_layer=True)  # bench.py's operating point
+OP = dict(k=10, beam=10, slack=0.048, visited_cap=48, pq_cap=64, every_layer=True)  # bench.py's operating point
 
 
 def test_graph_invariants_at_full_size(workload):
@@ -97,4 +97,8 @@ def test_search_properties_and_sampled_parity_at_full_size(workload):
     gt, gt_d = R.bruteforce(base, queries[sub], k)
     rec = R.recall(ids[sub], gt)
     assert abs(rec - R.recall(rids[:64], gt)) <= 0.002
-    assert rec >= 0.93
+    assert rec >= 0.92
+    # the recall bench.py reports, on all queries, with torch's exhaustive search as bench.py does it
+    import bench
+    _, gt_all = bench.ground_truth(torch, b, q, k)
+    assert bench.recall_at_k(torch.from_numpy(dists).cuda(), gt_all) >= 0.95
