@@ -281,6 +281,8 @@ def test_build_quality_and_recall(ggnn, R, sift10k, sift10k_gt):
     dict(N=900, D=1024, K=16, L=2, s=32, kind="int"),           # the longest float32 row
     dict(N=1000, D=256, K=24, L=2, s=32, kind="u8"),            # the longest uint8 row
     dict(N=1000, D=256, K=24, L=2, s=32, kind="real"),          # the longest float32 row with 8 lanes per row
+    dict(N=3000, D=16, K=64, L=2, s=64, kind="int"),            # the largest out-degree and segment size
+    dict(N=4000, D=8, K=8, L=5, s=8, kind="real"),              # five levels of small segments
 ])
 def test_full_build_matches_oracle_on_varied_shapes(ggnn, R, case):
     rng = np.random.default_rng(case["N"])
