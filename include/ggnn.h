@@ -11,7 +11,8 @@
  *  - Pointers named *_dev are device (HBM) pointers owned by the caller; pointers named
  *    *_host are host pointers owned by the caller.  The library never frees them.
  *  - Vectors are row-major, D elements per row, rows 16-byte aligned (D*sizeof(element)
- *    must be a multiple of 16).  Ids are int32; byte offsets are 64-bit.
+ *    must be a multiple of 16).  Ids are int32; offsets into the graph's own arrays are 64-bit,
+ *    byte offsets into the vector array 32-bit (hence the size limit below).
  *  - `base_dev` is BORROWED by the graph and must outlive it (it is not copied, except
  *    that a cosine graph owns a unit-length float32 copy).
  *  - All work is issued on the stream given at creation (or per call for queries); calls
