@@ -17,7 +17,9 @@ namespace ggnn {
 
 constexpr u64 kEmptyKey = ~0ull;
 
-// whole-wave shift by one lane (GFX9 DPP wave_shr:1 / wave_shl:1); the vacated lane gets `fill`
+// whole-wave shift by one lane (GFX9 DPP wave_shr:1 / wave_shl:1); the vacated lane gets `fill`, and so
+// does every enabled lane whose source lane is disabled (a DPP move leaves such a lane at its old value,
+// which is `fill` here): the sorted insertions below rely on that
 __device__ __forceinline__ u64 wave_shift_up(u64 v, u64 fill) {
   int lo = __builtin_amdgcn_update_dpp((int)(uint32_t)fill, (int)(uint32_t)v, 0x138, 0xf, 0xf, false);
   int hi = __builtin_amdgcn_update_dpp((int)(uint32_t)(fill >> 32), (int)(uint32_t)(v >> 32), 0x138, 0xf, 0xf, false);
@@ -189,8 +191,9 @@ struct RegCacheT {
     const int lane = lane_id();
     const bool lt = L < key;
     const int pos = __popcll(__ballot(lt));
-    const u64 up = wave_shift_up(L, key);
-    L = lt ? L : (lane == pos ? key : up);
+    // The entries not below the key move up one lane, with only those lanes enabled: the first of
+    // them finds its source lane disabled and takes the shift's fill value, the key itself.
+    if (!lt) L = wave_shift_up(L, key);
     if (cap < kWave && lane >= cap) L = kEmptyKey;
     if (pos < cap && n < cap) n++;
   }
@@ -206,6 +209,12 @@ struct RegCacheT {
       pos += __popcll(__ballot(lt[e]));
     }
     if (pos >= B) return;
+    if (NB == 1) {  // as list_insert: only the entries not below the key are enabled for the shift
+      if (!lt[0]) best[0] = wave_shift_up(best[0], key);
+      if (lane >= B) best[0] = kEmptyKey;
+      if (nb < B) nb++;
+      return;
+    }
     u64 carry = key;
 #pragma unroll
     for (int e = 0; e < NB; e++) {
