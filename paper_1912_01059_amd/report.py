@@ -72,9 +72,9 @@ def main():
     ap.add_argument("--n", type=int, default=None)
     ap.add_argument("--levels", type=int, default=3)
     ap.add_argument("--build-iter", type=int, default=192)
-    ap.add_argument("--slack", type=float, default=0.05)
+    ap.add_argument("--slack", type=float, default=0.048)
     ap.add_argument("--beam", type=int, default=10)
-    ap.add_argument("--limit", type=int, default=64)
+    ap.add_argument("--limit", type=int, default=48)
     ap.add_argument("--direct", action="store_true", help="drop from the top layer straight to the bottom one")
     a = ap.parse_args()
 
