@@ -185,7 +185,8 @@ def main():
         large = {"queries": len(qn), "qps": round(len(qn) / lms * 1e3, 1), "kernel_ms": round(lms, 3),
                  "achieved_GBps": round(lbytes / (lms * 1e-3) / 1e9, 1),
                  "frac_of_hbm_peak": round(lbytes / (lms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                 "note": "algorithmic bytes: about a quarter of the gathered rows are served by the L2"}
+                 "note": "two launches with the bottom-layer searches ordered by region (one part per XCD); algorithmic "
+                         "bytes: a good part of the gathered rows is served by the L2"}
         del ql, lids, ld, lcnt
     gather_ceiling = None
     if D * esize <= 512 and metric == ggnn.L2:  # the probe reads rows of up to 512 bytes of the array as given

@@ -189,6 +189,14 @@ int ggnn_graph_export_inv_count(const ggnn_graph* g, int32_t layer, int32_t* cou
  * Results do not depend on it.  Process-wide. */
 int ggnn_set_cache_mode(int32_t mode);
 
+/* Batches of at least `min_queries` user queries that search every layer (register cache, three levels or
+ * more) are answered in two launches: the upper layers, then the bottom layer with the queries ordered
+ * by the layer-1 point each arrived at, one contiguous part of that order per XCD, so that queries of
+ * one region share an L2 cache.  Results and counters do not depend on it; the workspace comes from the
+ * stream's memory pool (hipMallocAsync) and is returned to it.  Default 24576; 0 restores the default, a
+ * value above every batch size turns the two-launch path off.  Process-wide. */
+int ggnn_set_split_threshold(int64_t min_queries);
+
 /* Measurement aid (not part of the method): gathers rows ids_dev[0..n_ids) (each in [0, n_rows), not
  * checked) of rows_dev (row_bytes per row, multiple of 16, <= 512) with the search kernels' access
  * pattern, rows_per_wave rows per wavefront, and writes one word per lane to out_dev

@@ -159,13 +159,58 @@ int make_search_params(int B, int P, int V, int max_iter, float tau, float dnn, 
   return GGNN_OK;
 }
 
-hipError_t launch_query(const GraphDev& G, int dtype, int metric, const void* queries, int64_t Q, int k,
-                        const SearchParams& sp, int every_layer, int32_t* ids, float* dists, uint32_t* counters,
-                        hipStream_t stream) {
+hipError_t launch_query_whole(const GraphDev& G, int dtype, int metric, const void* queries, int64_t Q, int k,
+                              const SearchParams& sp, int every_layer, int32_t* ids, float* dists, uint32_t* counters,
+                              hipStream_t stream) {
   const int slots = register_slots(sp, true);
   if (slots == 1) return launch_query_reg(G, dtype, metric, queries, Q, k, sp, every_layer, ids, dists, counters, stream);
   if (slots == 2) return launch_query_reg2(G, dtype, metric, queries, Q, k, sp, every_layer, ids, dists, counters, stream);
   return launch_query_lds(G, dtype, metric, queries, Q, k, sp, every_layer, ids, dists, counters, stream);
+}
+
+// Batches of this many queries and more are answered in two launches with the bottom-layer searches
+// ordered by region (see SplitBufs); smaller ones gain nothing from it.
+constexpr int64_t kSplitMinQueries = 24576;
+int64_t g_split_min_queries = kSplitMinQueries;
+
+hipError_t launch_query(const GraphDev& G, int dtype, int metric, const void* queries, int64_t Q, int k,
+                        const SearchParams& sp, int every_layer, int32_t* ids, float* dists, uint32_t* counters,
+                        hipStream_t stream) {
+  SplitBufs sb = {};
+  const int slots = register_slots(sp, true);
+  const bool split = every_layer && G.L >= 3 && !sp.start && slots >= 1 && Q >= g_split_min_queries;
+  if (!split) return launch_query_whole(G, dtype, metric, queries, Q, k, sp, every_layer, ids, dists, counters, stream);
+  // workspace from the stream's memory pool: lists, counters, keys, order, bins
+  int shift = 0;
+  while (((G.n[1] - 1) >> shift) >= kSortBins) shift++;
+  const int nbins = (int)(((G.n[1] - 1) >> shift) + 1);
+  sb.Q = Q;
+  sb.state_keys = (slots + 1) * kWave;
+  const size_t state_bytes = (size_t)Q * sb.state_keys * sizeof(u64);
+  const size_t meta_bytes = (size_t)Q * 8 * sizeof(int32_t);
+  const size_t q_bytes = (((size_t)Q * sizeof(int32_t)) + 255) / 256 * 256;
+  const size_t total = state_bytes + meta_bytes + 2 * q_bytes + ((size_t)nbins + 1) * sizeof(int32_t);
+  unsigned char* ws = nullptr;
+  if (hipMallocAsync((void**)&ws, total, stream) != hipSuccess) {
+    (void)hipGetLastError();  // no workspace: the one-launch path needs none
+    return launch_query_whole(G, dtype, metric, queries, Q, k, sp, every_layer, ids, dists, counters, stream);
+  }
+  sb.state = (u64*)ws;
+  sb.meta = (int32_t*)(ws + state_bytes);
+  sb.key = (int32_t*)(ws + state_bytes + meta_bytes);
+  int32_t* order = (int32_t*)(ws + state_bytes + meta_bytes + q_bytes);
+  int32_t* bins = (int32_t*)(ws + state_bytes + meta_bytes + 2 * q_bytes);
+  sb.phase = 1;
+  hipError_t e = launch_query_split(slots, G, dtype, metric, queries, Q, k, sp, ids, dists, counters, sb, stream);
+  if (e == hipSuccess) e = launch_sort_by_key(sb.key, Q, shift, nbins, bins, order, stream);
+  if (e == hipSuccess) {
+    sb.phase = 2;
+    sb.order = order;
+    sb.per = (int32_t)((Q + kXcds - 1) / kXcds);
+    e = launch_query_split(slots, G, dtype, metric, queries, Q, k, sp, ids, dists, counters, sb, stream);
+  }
+  const hipError_t f = hipFreeAsync(ws, stream);
+  return e != hipSuccess ? e : f;
 }
 hipError_t launch_merge(const GraphDev& G, int dtype, int metric, int l_top, int l_m, const SearchParams& sp,
                         int32_t* out_rows, float* dnn1, unsigned long long* work, hipStream_t stream) {
@@ -259,6 +304,12 @@ int ggnn_gather_probe(const void* rows_dev, int64_t n_rows, int32_t row_bytes, c
 int ggnn_set_cache_mode(int32_t mode) {
   if (mode != 0 && mode != 1) return fail(GGNN_ERR_INVALID, "cache mode %d is neither 0 nor 1", mode);
   g_cache_mode = mode;
+  return GGNN_OK;
+}
+
+int ggnn_set_split_threshold(int64_t min_queries) {
+  if (min_queries < 0) return fail(GGNN_ERR_INVALID, "min_queries = %lld is negative", (long long)min_queries);
+  g_split_min_queries = min_queries == 0 ? kSplitMinQueries : min_queries;
   return GGNN_OK;
 }
 

@@ -17,6 +17,50 @@ hipError_t launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t stream)
   return hipGetLastError();
 }
 
+// Counting sort of the query numbers by key >> shift: histogram, exclusive scan (one workgroup),
+// scatter.  Used to order a large batch by the layer-1 point each query arrived at.
+__global__ void sort_hist_kernel(const int32_t* __restrict__ key, int64_t Q, int shift, int32_t* __restrict__ bins) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < Q) atomicAdd(&bins[key[i] >> shift], 1);
+}
+__global__ __launch_bounds__(1024) void sort_scan_kernel(int32_t* __restrict__ bins, int nbins) {
+  __shared__ int32_t part[1024];
+  const int t = threadIdx.x;
+  const int per = (nbins + 1023) / 1024;
+  const int lo = t * per, hi = (lo + per < nbins) ? lo + per : nbins;
+  int32_t sum = 0;
+  for (int i = lo; i < hi; i++) sum += bins[i];
+  part[t] = sum;
+  __syncthreads();
+  for (int d = 1; d < 1024; d <<= 1) {  // inclusive scan of the partial sums
+    const int32_t v = (t >= d) ? part[t - d] : 0;
+    __syncthreads();
+    part[t] += v;
+    __syncthreads();
+  }
+  int32_t run = part[t] - sum;  // exclusive prefix of this thread's bins
+  for (int i = lo; i < hi; i++) {
+    const int32_t c = bins[i];
+    bins[i] = run;
+    run += c;
+  }
+}
+__global__ void sort_scatter_kernel(const int32_t* __restrict__ key, int64_t Q, int shift, int32_t* __restrict__ bins,
+                                    int32_t* __restrict__ order) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < Q) order[atomicAdd(&bins[key[i] >> shift], 1)] = (int32_t)i;
+}
+hipError_t launch_sort_by_key(const int32_t* key, int64_t Q, int shift, int nbins, int32_t* bins, int32_t* order,
+                              hipStream_t stream) {
+  hipError_t e = launch_fill_i32(bins, nbins + 1, 0, stream);
+  if (e != hipSuccess) return e;
+  const unsigned blocks = (unsigned)((Q + 255) / 256);
+  sort_hist_kernel<<<blocks, 256, 0, stream>>>(key, Q, shift, bins);
+  sort_scan_kernel<<<1, 1024, 0, stream>>>(bins, nbins);
+  sort_scatter_kernel<<<blocks, 256, 0, stream>>>(key, Q, shift, bins, order);
+  return hipGetLastError();
+}
+
 // unit-length float32 copy of the base rows (cosine): x / sqrt(sum x^2), the sum taken in
 // the fixed order of every distance; RL lanes per row (8, or 64 for rows longer than 1024 bytes)
 template <int RL>

@@ -40,6 +40,21 @@ struct SearchParams {
   int32_t n_start;
 };
 
+// A large batch of user queries is answered in two launches: the upper layers first, then the bottom
+// layer with the queries ordered by the layer-1 point they arrived at, one contiguous part of that
+// order per XCD (workgroups go to the XCDs in turn), so that queries of one region share an L2.
+struct SplitBufs {
+  int32_t phase;         // 0: whole search in one launch, 1: upper layers, 2: bottom layer
+  int32_t per;           // phase 2: queries per XCD part
+  int64_t Q;
+  u64* state;            // Q x state_keys keys: best, then prioq, as the wavefront holds them
+  int32_t state_keys;
+  int32_t* meta;         // Q x 8: nb, np, pops, evals, gathers
+  int32_t* key;          // Q: layer-1 id of the best point so far (phase 1 writes)
+  const int32_t* order;  // Q: query numbers in sorted order (phase 2 reads)
+};
+constexpr int kXcds = 8;
+
 // ---- packed keys: (float32 distance, int32 id) ordered as one unsigned 64-bit integer.
 // Distances are >= +0, so their bit patterns order like the values; +inf sorts last.
 __device__ __forceinline__ u64 make_key(float d, int32_t id) {

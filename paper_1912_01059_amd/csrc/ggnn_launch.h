@@ -41,6 +41,10 @@ GGNN_SEARCH_LAUNCHERS(_reg)
 hipError_t launch_query_reg2(const GraphDev& G, int dtype, int metric, const void* queries, int64_t Q, int k,
                              const SearchParams& sp, int every_layer, int32_t* ids, float* dists, uint32_t* counters,
                              hipStream_t stream);
+// ggnn_search_split.hip: launch sb.phase (1 or 2) of a large batch; slots = registers per lane of best (1 or 2)
+hipError_t launch_query_split(int slots, const GraphDev& G, int dtype, int metric, const void* queries, int64_t Q, int k,
+                              const SearchParams& sp, int32_t* ids, float* dists, uint32_t* counters,
+                              const SplitBufs& sb, hipStream_t stream);
 GGNN_SEARCH_LAUNCHERS(_lds)
 #undef GGNN_SEARCH_LAUNCHERS
 
@@ -50,6 +54,11 @@ hipError_t launch_gather_probe(const void* rows, int row_bytes, const int32_t* i
 hipError_t launch_merge_shards(int S, int64_t Q, int k, const int32_t* ids, const float* dists, const int32_t* offsets,
                                int32_t* out_ids, float* out_dists, hipStream_t stream);
 hipError_t launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t stream);
+// order[0..Q) := the numbers 0..Q-1 sorted by key >> shift (a counting sort; the order within one value is
+// not defined); bins: nbins + 1 ints of scratch, nbins <= kSortBins
+constexpr int kSortBins = 65536;
+hipError_t launch_sort_by_key(const int32_t* key, int64_t Q, int shift, int nbins, int32_t* bins, int32_t* order,
+                              hipStream_t stream);
 hipError_t launch_normalise(const void* base, int dtype, int64_t N, int D, float* out, hipStream_t stream);
 hipError_t launch_select(const GraphDev& G, int l_top, const float* dnn1, int32_t* to_lower, int32_t* to_base,
                          hipStream_t stream);

@@ -447,6 +447,25 @@ struct RegCacheT {
     GGNN_TICK(7);  // rejected filter
   }
 
+  // the lists and counters of a search that continues in another launch
+  __device__ __forceinline__ void save_state(u64* __restrict__ st, int32_t* __restrict__ meta) const {
+    const int lane = lane_id();
+#pragma unroll
+    for (int e = 0; e < NB; e++) st[e * kWave + lane] = best[e];
+    st[NB * kWave + lane] = pq;
+    if (lane == 0) {
+      meta[0] = nb; meta[1] = np; meta[2] = (int32_t)pops; meta[3] = (int32_t)evals; meta[4] = (int32_t)gathers;
+    }
+  }
+  __device__ __forceinline__ void load_state(const u64* __restrict__ st, const int32_t* __restrict__ meta) {  // after init()
+    const int lane = lane_id();
+#pragma unroll
+    for (int e = 0; e < NB; e++) best[e] = st[e * kWave + lane];
+    pq = st[NB * kWave + lane];
+    nb = meta[0]; np = meta[1]; pops = (uint32_t)meta[2]; evals = (uint32_t)meta[3]; gathers = (uint32_t)meta[4];
+  }
+  __device__ int32_t first_id() const { return nb > 0 ? key_id(read_lane_u64(best[0], 0)) : 0; }
+
   // results
   __device__ void store_results(int k, int32_t* __restrict__ ids, float* __restrict__ dists) const {
     const int lane = lane_id();

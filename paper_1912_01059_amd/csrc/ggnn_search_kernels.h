@@ -51,13 +51,22 @@ __device__ inline void descend(C& c, const GraphDev& G, int layer, const QueryRe
   }
 }
 
-template <class C, int DT, int NCH, int METRIC>
-__global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(SearchWavesPerSimd<DT, NCH>::value))) void query_kernel(GraphDev G, const uint8_t* __restrict__ queries, int k,
-                                                      SearchParams sp, int every_layer, int32_t* __restrict__ ids,
-                                                      float* __restrict__ dists, uint32_t* __restrict__ counters) {
+// PHASE 0: the whole search; 1: the layers above the bottom one, after which the lists are put aside;
+// 2: the bottom layer, from the lists put aside, in the order given (see SplitBufs).
+template <class C, int DT, int NCH, int METRIC, int PHASE>
+__device__ __forceinline__ void query_body(const GraphDev& G, const uint8_t* __restrict__ queries, int k,
+                                           const SearchParams& sp, int every_layer, int32_t* __restrict__ ids,
+                                           float* __restrict__ dists, uint32_t* __restrict__ counters,
+                                           const SplitBufs& sb) {
   extern __shared__ __align__(16) unsigned char lds[];
   const int lane = lane_id();
-  const int64_t qi = blockIdx.x;
+  int64_t qi = blockIdx.x;
+  if (PHASE == 2) {
+    // XCD x takes part x of the sorted order: workgroup b is the (b / 8)-th of XCD b % 8
+    const int64_t i = (int64_t)(blockIdx.x % kXcds) * sb.per + blockIdx.x / kXcds;
+    if (blockIdx.x / kXcds >= (unsigned)sb.per || i >= sb.Q) return;
+    qi = sb.order[i];
+  }
   C c;
   c.bind(lds, sp);
   c.init();
@@ -72,17 +81,29 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(SearchWav
     c.template fetch<DT, NCH, METRIC, kPasses>(G, 0, lane < sp.n_start ? sp.start[lane] : -1, q, -1);
     descend<C, DT, NCH, METRIC>(c, G, 0, q, -1);
   } else {
-  // start points: the s points of the top layer (Sec. 3.1, Sec. 4.4)
-  c.template fetch<DT, NCH, METRIC, kPasses>(G, top, lane < G.s ? lane : -1, q, -1);
-  if (every_layer) {
-    for (int l = top - 1; l >= 0; l--) {
-      c.transform(G.to_lower[l + 1]);
-      descend<C, DT, NCH, METRIC>(c, G, l, q, -1);
+    // start points: the s points of the top layer (Sec. 3.1, Sec. 4.4), or, in the second of two
+    // launches, the lists the first one put aside after the upper layers
+    bool resumed = false;
+    if constexpr (C::kInRegisters && PHASE == 2) {
+      c.load_state(sb.state + (size_t)qi * sb.state_keys, sb.meta + (size_t)qi * 8);
+      resumed = true;
     }
-  } else {
-    c.transform(G.to_base[top]);
-    descend<C, DT, NCH, METRIC>(c, G, 0, q, -1);
+    if (!resumed) c.template fetch<DT, NCH, METRIC, kPasses>(G, top, lane < G.s ? lane : -1, q, -1);
+    if (every_layer) {
+      const int l_first = resumed ? 0 : top - 1, l_last = (PHASE == 1) ? 1 : 0;
+      for (int l = l_first; l >= l_last; l--) {
+        c.transform(G.to_lower[l + 1]);
+        descend<C, DT, NCH, METRIC>(c, G, l, q, -1);
+      }
+    } else {
+      c.transform(G.to_base[top]);
+      descend<C, DT, NCH, METRIC>(c, G, 0, q, -1);
+    }
   }
+  if constexpr (C::kInRegisters && PHASE == 1) {  // first of two launches: the search continues in the second
+    if (lane == 0) sb.key[qi] = c.first_id();
+    c.save_state(sb.state + (size_t)qi * sb.state_keys, sb.meta + (size_t)qi * 8);
+    return;
   }
   c.store_results(k, ids + (size_t)qi * k, dists + (size_t)qi * k);
 #ifdef GGNN_PHASE_TIMING
@@ -95,6 +116,18 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(SearchWav
     counters[4 * qi + 3] = 0;
   }
 }
+
+#define GGNN_QUERY_KERNEL(NAME, PHASE)                                                                              \
+  template <class C, int DT, int NCH, int METRIC>                                                                   \
+  __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(SearchWavesPerSimd<DT, NCH>::value))) void  \
+  NAME(GraphDev G, const uint8_t* __restrict__ queries, int k, SearchParams sp, int every_layer,                    \
+       int32_t* __restrict__ ids, float* __restrict__ dists, uint32_t* __restrict__ counters, SplitBufs sb) {       \
+    query_body<C, DT, NCH, METRIC, PHASE>(G, queries, k, sp, every_layer, ids, dists, counters, sb);                \
+  }
+GGNN_QUERY_KERNEL(query_kernel, 0)
+GGNN_QUERY_KERNEL(query_upper_kernel, 1)
+GGNN_QUERY_KERNEL(query_lower_kernel, 2)
+#undef GGNN_QUERY_KERNEL
 
 template <class C, int DT, int NCH, int METRIC>
 __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(SearchWavesPerSimd<DT, NCH>::value))) void merge_kernel(GraphDev G, int l_top, int l_m, SearchParams sp,
@@ -244,7 +277,24 @@ hipError_t launch_query_t(const GraphDev& G, int dtype, int metric, const void* 
   if (Q <= 0) return hipSuccess;
   const dim3 grid((unsigned)Q);
   const size_t lds = C::lds_bytes(sp);
-  GGNN_DISPATCH(C, query_kernel, G, (const uint8_t*)queries, k, sp, every_layer, ids, dists, counters);
+  const SplitBufs sb = {};
+  GGNN_DISPATCH(C, query_kernel, G, (const uint8_t*)queries, k, sp, every_layer, ids, dists, counters, sb);
+  return hipGetLastError();
+}
+// one of the two launches of a large batch (sb.phase 1 or 2; register cache only)
+template <class C>
+hipError_t launch_query_split_t(const GraphDev& G, int dtype, int metric, const void* queries, int64_t Q, int k,
+                                const SearchParams& sp, int32_t* ids, float* dists, uint32_t* counters,
+                                const SplitBufs& sb, hipStream_t stream) {
+  if (Q <= 0) return hipSuccess;
+  const dim3 grid((unsigned)(sb.phase == 2 ? (int64_t)kXcds * sb.per : Q));
+  const size_t lds = C::lds_bytes(sp);
+  const int every_layer = 1;
+  if (sb.phase == 1) {
+    GGNN_DISPATCH(C, query_upper_kernel, G, (const uint8_t*)queries, k, sp, every_layer, ids, dists, counters, sb);
+  } else {
+    GGNN_DISPATCH(C, query_lower_kernel, G, (const uint8_t*)queries, k, sp, every_layer, ids, dists, counters, sb);
+  }
   return hipGetLastError();
 }
 template <class C>

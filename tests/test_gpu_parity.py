@@ -371,3 +371,28 @@ def test_query_from_start_points(ggnn, R, sift10k, sift10k_oracle_graph):
         g.query(dev(queries[:4]), 10, 10, 0.4, start_ids=dev(np.array([10_000], np.int32)))
     with pytest.raises(ggnn.GgnnError):
         g.query(dev(queries[:4]), 10, 10, 0.4, start_ids=dev(np.arange(65, dtype=np.int32)))
+
+
+# ------------------------------------------------------------------------------ large batches in two launches
+
+def test_two_launch_path_matches_one_launch_and_oracle(ggnn, R, sift10k, sift10k_oracle_graph):
+    """Large batches are answered in two launches (upper layers; bottom layer in an order sorted by
+    region, one part per XCD).  Forced here for small batches: results and counters must be those of
+    the one-launch path and of the oracle."""
+    base, queries, cfg = sift10k
+    og = sift10k_oracle_graph
+    g = to_gpu_graph(ggnn, og, dev(base))
+    rng = np.random.default_rng(3)
+    for Q, k, beam, tau, P in [(997, 10, 10, 0.3, 64), (1000, 10, 100, 0.2, 64), (8, 5, 16, 0.5, 32), (3, 1, 1, 0.0, 64)]:
+        q = queries[rng.integers(0, len(queries), Q)].copy()
+        ids1, d1, c1 = g.query(dev(q), k, beam, tau, pq_cap=P, every_layer=True, counters=True)
+        ggnn.set_split_threshold(1)
+        try:
+            ids2, d2, c2 = g.query(dev(q), k, beam, tau, pq_cap=P, every_layer=True, counters=True)
+        finally:
+            ggnn.set_split_threshold(0)
+        assert torch.equal(ids1, ids2) and torch.equal(d1.view(torch.int32), d2.view(torch.int32))
+        assert torch.equal(c1, c2)
+        rids, rd, rcnt = og.query(q, k, beam, tau, pq_cap=P, every_layer=True, counters=True)
+        assert_same_results(ids2, d2, rids, rd)
+        check_counters(c2, rcnt)
