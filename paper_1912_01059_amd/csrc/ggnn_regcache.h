@@ -329,6 +329,7 @@ struct RegCacheT {
       alive = row != excl_row;
     }
     GGNN_TICK(1);  // adjacency row arrives
+    const bool bit = maybe_listed(p);  // read alongside the first probe, not after the last (any p indexes the map)
     bool seen_rejected = false;
     if (alive) {
       const int kind = probe(p);
@@ -338,7 +339,7 @@ struct RegCacheT {
     GGNN_TICK(2);  // hash probe
     // membership in best / prioq: only proposals whose bucket bit is set can be listed;
     // each of those is broadcast and compared with the entry every lane holds
-    u64 cand = __ballot(alive && maybe_listed(p));
+    u64 cand = __ballot(alive && bit);
     u64 known = 0;
     while (cand) {
       const int j = __builtin_ctzll(cand);
