@@ -294,11 +294,16 @@ __device__ inline void cache_transform(Cache& c, const int32_t* __restrict__ tab
 
 // ---- distances ------------------------------------------------------------------------
 // Row formats: 0 = float32 (4 per 16-byte chunk), 8 lanes per row; 1 = uint8 (16 per chunk), 8 lanes
-// per row; 2 = float32, the whole wavefront per row (rows longer than 1024 bytes).
+// per row; 2 = float32, the whole wavefront per row (rows longer than 1024 bytes); 3 = uint8 with an
+// integer query (below).
 template <int DT> struct Elem;
 template <> struct Elem<0> { static constexpr int per_chunk = 4, lanes = kRowLanes; };
 template <> struct Elem<1> { static constexpr int per_chunk = 16, lanes = kRowLanes; };
 template <> struct Elem<2> { static constexpr int per_chunk = 4, lanes = kWideRowLanes; };
+// 3 = uint8 rows against a uint8 query (user queries and Merge; the sym query is a real-valued point
+// and takes format 1): sum (q-x)^2 = sum q^2 + sum x^2 - 2 sum q x in exact integer arithmetic with
+// 4-way byte dot products.  The sum is below 2^24, so it is the float32 sum of format 1 bit for bit.
+template <> struct Elem<3> { static constexpr int per_chunk = 16, lanes = kRowLanes; };
 // rows a wavefront takes per gather instruction, and gather instructions issued before the first use
 template <int DT, int PASSES> struct RowSched {
   static constexpr int rows_per_pass = kWave / Elem<DT>::lanes;
@@ -355,40 +360,70 @@ template <int DT, int NCH>
 struct QueryRegs {
   float v[NCH * Elem<DT>::per_chunk];
 };
+template <int NCH>
+struct QueryRegs<3, NCH> {
+  uint32_t w[NCH * 4];  // the query's bytes, four to a word
+  uint32_t qq;          // sum of the squares of this lane's query elements
+};
 
 template <int DT, int NCH>
 __device__ inline void load_query(QueryRegs<DT, NCH>& q, const uint8_t* row, int nchunks) {
   constexpr int RL = Elem<DT>::lanes;
   const int sub = lane_id() & (RL - 1);
+  if constexpr (DT == 3) q.qq = 0;
 #pragma unroll
   for (int c = 0; c < NCH; c++) {
     int chunk = c * RL + sub;
     uint4 raw = make_uint4(0, 0, 0, 0);
     if (chunk < nchunks) raw = *(const uint4*)(row + (size_t)chunk * 16);
-    chunk_to_float<DT>(raw, &q.v[c * Elem<DT>::per_chunk]);  // chunks past the row read as zeros
+    if constexpr (DT == 3) {
+      const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+      for (int i = 0; i < 4; i++) {
+        q.w[c * 4 + i] = w[i];
+        q.qq = __builtin_amdgcn_udot4(w[i], w[i], q.qq, false);
+      }
+    } else {
+      chunk_to_float<DT>(raw, &q.v[c * Elem<DT>::per_chunk]);  // chunks past the row read as zeros
+    }
   }
 }
 
 // one row against the query: METRIC 0: sum (q-x)^2, 1: sum q*x, in the fixed order
 template <int DT, int NCH, int METRIC>
 __device__ __forceinline__ float row_sum(const QueryRegs<DT, NCH>& q, const uint4 (&raw)[NCH]) {
-  constexpr int E = Elem<DT>::per_chunk;
-  float acc = 0.0f;
+  if constexpr (DT == 3) {
+    static_assert(METRIC == 0, "integer rows have no cosine distance");
+    uint32_t xx = q.qq, qx = 0;
 #pragma unroll
-  for (int c = 0; c < NCH; c++) {
-    float x[E];
-    chunk_to_float<DT>(raw[c], x);
+    for (int c = 0; c < NCH; c++) {
+      const uint32_t w[4] = {raw[c].x, raw[c].y, raw[c].z, raw[c].w};
 #pragma unroll
-    for (int e = 0; e < E; e++) {
-      if (METRIC == 0) {
-        float t = q.v[c * E + e] - x[e];
-        acc = __builtin_fmaf(t, t, acc);
-      } else {
-        acc = __builtin_fmaf(q.v[c * E + e], x[e], acc);
+      for (int i = 0; i < 4; i++) {
+        xx = __builtin_amdgcn_udot4(w[i], w[i], xx, false);
+        qx = __builtin_amdgcn_udot4(q.w[c * 4 + i], w[i], qx, false);
       }
     }
+    return row_reduce((float)(xx - 2u * qx));  // per lane at most 32 * 255^2: exact in float32, as is the total
+  } else {
+    constexpr int E = Elem<DT>::per_chunk;
+    float acc = 0.0f;
+#pragma unroll
+    for (int c = 0; c < NCH; c++) {
+      float x[E];
+      chunk_to_float<DT>(raw[c], x);
+#pragma unroll
+      for (int e = 0; e < E; e++) {
+        if (METRIC == 0) {
+          float t = q.v[c * E + e] - x[e];
+          acc = __builtin_fmaf(t, t, acc);
+        } else {
+          acc = __builtin_fmaf(q.v[c * E + e], x[e], acc);
+        }
+      }
+    }
+    return row_reduce_t<Elem<DT>::lanes>(acc);
   }
-  return row_reduce_t<Elem<DT>::lanes>(acc);
 }
 // from the sum to the distance: METRIC 0: sqrt(sum), 1: max(0, 1 - sum)
 template <int METRIC>

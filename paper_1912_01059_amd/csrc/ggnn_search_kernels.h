@@ -72,7 +72,7 @@ __device__ __forceinline__ void query_body(const GraphDev& G, const uint8_t* __r
   c.init();
   QueryRegs<DT, NCH> q;
   load_query<DT, NCH>(q, queries + (size_t)qi * (size_t)G.row_bytes, G.nchunks);
-  if (METRIC == 1) normalise_query<DT, NCH>(q);
+  if constexpr (METRIC == 1) normalise_query<DT, NCH>(q);
 
   const int top = G.L - 1;
   if (sp.start) {
@@ -241,6 +241,7 @@ __global__ __launch_bounds__(kWave) void sym_search_kernel(GraphDev G, int layer
 }
 
 // ---- dispatch over element type, chunks per lane and metric ---------------------------
+// (kU8Format, defined by the launcher: 3 where the query is a uint8 vector itself, 1 for the sym query)
 // (rows of at most 1024 bytes: 8 lanes per row; longer float32 rows: the whole wavefront per row)
 #define GGNN_LAUNCH(C, KERNEL, DT, NCH, M, ...) KERNEL<C, DT, NCH, M><<<grid, kWave, lds, stream>>>(__VA_ARGS__)
 #define GGNN_DISPATCH(C, KERNEL, ...)                                                       \
@@ -264,8 +265,8 @@ __global__ __launch_bounds__(kWave) void sym_search_kernel(GraphDev G, int layer
       else if (wide <= 4) GGNN_LAUNCH(C, KERNEL, 2, 4, 0, __VA_ARGS__);                     \
       else return hipErrorInvalidValue;                                                     \
     } else {                                                                                \
-      if (need <= 1) GGNN_LAUNCH(C, KERNEL, 1, 1, 0, __VA_ARGS__);                          \
-      else if (need <= 2) GGNN_LAUNCH(C, KERNEL, 1, 2, 0, __VA_ARGS__);                     \
+      if (need <= 1) GGNN_LAUNCH(C, KERNEL, kU8Format, 1, 0, __VA_ARGS__);                  \
+      else if (need <= 2) GGNN_LAUNCH(C, KERNEL, kU8Format, 2, 0, __VA_ARGS__);             \
       else return hipErrorInvalidValue;                                                     \
     }                                                                                       \
   } while (0)
@@ -277,6 +278,7 @@ hipError_t launch_query_t(const GraphDev& G, int dtype, int metric, const void* 
   if (Q <= 0) return hipSuccess;
   const dim3 grid((unsigned)Q);
   const size_t lds = C::lds_bytes(sp);
+  constexpr int kU8Format = 3;
   const SplitBufs sb = {};
   GGNN_DISPATCH(C, query_kernel, G, (const uint8_t*)queries, k, sp, every_layer, ids, dists, counters, sb);
   return hipGetLastError();
@@ -289,6 +291,7 @@ hipError_t launch_query_split_t(const GraphDev& G, int dtype, int metric, const 
   if (Q <= 0) return hipSuccess;
   const dim3 grid((unsigned)(sb.phase == 2 ? (int64_t)kXcds * sb.per : Q));
   const size_t lds = C::lds_bytes(sp);
+  constexpr int kU8Format = 3;
   const int every_layer = 1;
   if (sb.phase == 1) {
     GGNN_DISPATCH(C, query_upper_kernel, G, (const uint8_t*)queries, k, sp, every_layer, ids, dists, counters, sb);
@@ -302,6 +305,7 @@ hipError_t launch_merge_t(const GraphDev& G, int dtype, int metric, int l_top, i
                           int32_t* out_rows, float* dnn1, unsigned long long* work, hipStream_t stream) {
   const dim3 grid((unsigned)G.n[l_m]);
   const size_t lds = C::lds_bytes(sp);
+  constexpr int kU8Format = 3;
   GGNN_DISPATCH(C, merge_kernel, G, l_top, l_m, sp, out_rows, dnn1, work);
   return hipGetLastError();
 }
@@ -311,6 +315,7 @@ hipError_t launch_sym_search_t(const GraphDev& G, int dtype, int metric, int lay
                                hipStream_t stream) {
   const dim3 grid((unsigned)G.n[layer]);
   const size_t lds = C::lds_bytes(sp);
+  constexpr int kU8Format = 1;
   GGNN_DISPATCH(C, sym_search_kernel, G, layer, round, w_mid, sp, sb, work);
   return hipGetLastError();
 }
