@@ -70,9 +70,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy (reference for hardware byte counters)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample", type=int, default=2000)
-    ap.add_argument("--cpu-exhaustive", type=int, default=64, help="queries of the oracle's timed exhaustive search (0 = skip)")
-    ap.add_argument("--cpu-build-n", type=int, default=10_000,
+    ap.add_argument("--cpu-sample", type=int, default=10_000, help="queries of the oracle's timed search")
+    ap.add_argument("--cpu-exhaustive", type=int, default=128, help="queries of the oracle's timed exhaustive search (0 = skip)")
+    ap.add_argument("--cpu-build-n", type=int, default=100_000,
                     help="points of the oracle's timed construction (0 = skip; above 10 000: a subset of the workload)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -262,7 +262,7 @@ def main():
                "identical_to_gpu": same, "ground_truth_matches_oracle_exhaustive_search": gt_ok}
         # context figures (the paper's CPU references ran on one thread): the same search on one thread,
         # the oracle's exhaustive search, and the oracle's construction of the small configuration
-        n1 = min(500, ns)
+        n1 = min(2000, ns)
         R.lib().ggnn_ref_set_num_threads(1)
         t0 = time.perf_counter()
         og.query(queries_np[:n1], k, chosen["beam"], chosen["slack"], pq_cap=chosen["pq_cap"],
