@@ -122,15 +122,22 @@ def merge_shards(ids, dists, offsets):
 
 class ShardedIndex:
     """Sec. 4.5 on one GPU: the base set is cut into S contiguous shards, each with its own graph;
-    a query batch is answered on every shard and the answers are merged on the GPU."""
+    a query batch is answered on every shard and the answers are merged on the GPU.  The S searches
+    are independent: each runs on a stream of its own (default priority), so that the tail of one
+    overlaps the start of the next; the merge waits for all of them on the caller's stream."""
 
-    def __init__(self, base, shards, K, levels, **build_args):
+    def __init__(self, base, shards, K, levels, progress=None, **build_args):
         import torch
         N = base.shape[0]
         bounds = [N * i // shards for i in range(shards + 1)]
         self.parts = [base[bounds[i]:bounds[i + 1]].contiguous() for i in range(shards)]
         self.offsets = torch.tensor(bounds[:-1], dtype=torch.int32, device=base.device)
-        self.graphs = [build(p, K, levels, **build_args) for p in self.parts]
+        self.graphs = []
+        for i, p in enumerate(self.parts):
+            self.graphs.append(build(p, K, levels, **build_args))
+            if progress is not None:
+                progress(i, self.graphs[-1])  # called after each shard's construction
+        self.streams = [torch.cuda.Stream(device=base.device) for _ in self.graphs]
 
     def query(self, queries, k, beam, slack, **query_args):
         import torch
@@ -138,8 +145,18 @@ class ShardedIndex:
         S = len(self.graphs)
         ids = torch.empty((S, Q, k), dtype=torch.int32, device=queries.device)
         dists = torch.empty((S, Q, k), dtype=torch.float32, device=queries.device)
+        cur = torch.cuda.current_stream(queries.device)
+        ready = torch.cuda.Event()
+        ready.record(cur)
         for s, g in enumerate(self.graphs):
-            g.query(queries, k, beam, slack, out=(ids[s], dists[s]), **query_args)
+            st = self.streams[s]
+            st.wait_event(ready)
+            for t in (queries, ids, dists):
+                t.record_stream(st)
+            g.query(queries, k, beam, slack, out=(ids[s], dists[s]), stream=st.cuda_stream, asynchronous=True, **query_args)
+            done = torch.cuda.Event()
+            done.record(st)
+            cur.wait_event(done)
         return merge_shards(ids, dists, self.offsets)
 
 
