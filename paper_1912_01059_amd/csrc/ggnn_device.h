@@ -307,7 +307,7 @@ template <> struct Elem<3> { static constexpr int per_chunk = 16, lanes = kRowLa
 // rows a wavefront takes per gather instruction, and gather instructions issued before the first use
 template <int DT, int PASSES> struct RowSched {
   static constexpr int rows_per_pass = kWave / Elem<DT>::lanes;
-  static constexpr int passes = (Elem<DT>::lanes == kWave) ? 2 * PASSES : PASSES;
+  static constexpr int passes = (Elem<DT>::lanes == kWave) ? 3 * PASSES : PASSES;
 };
 
 template <int DT>
