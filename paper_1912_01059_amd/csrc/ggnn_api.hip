@@ -35,7 +35,7 @@ int fail(int code, const char* fmt, ...) {
     if (e_ != hipSuccess) return fail(GGNN_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_));       \
   } while (0)
 
-constexpr size_t kMaxLds = 64 * 1024;
+constexpr size_t kMaxLds = 160 * 1024;  // LDS of a compute unit on gfx950, all of which one workgroup may take
 int g_cache_mode = 0;  // 0: registers whenever best and prioq fit 64 entries, 1: always LDS
 
 uint64_t mix64_host(uint64_t x) {

@@ -78,7 +78,7 @@ def test_query_small_capacities_and_iteration_limit(ggnn, R, sift10k, sift10k_or
     og = sift10k_oracle_graph
     g = to_gpu_graph(ggnn, og, dev(base))
     q = dev(queries[:300])
-    for P, V, it in [(4, 16, 16), (8, 64, 10), (100, 500, 500), (64, 384, 1)]:
+    for P, V, it in [(4, 16, 16), (8, 64, 10), (100, 500, 500), (64, 384, 1), (64, 5000, 5000), (100, 9000, 9000)]:
         ids, d, cnt = g.query(q, 10, 10, 0.4, pq_cap=P, visited_cap=V, max_iter=it, every_layer=True, counters=True)
         rids, rd, rcnt = og.query(queries[:300], 10, 10, 0.4, pq_cap=P, visited_cap=V, max_iter=it, every_layer=True,
                                   counters=True)
@@ -163,7 +163,7 @@ def test_query_edge_cases(ggnn, R, sift10k, sift10k_oracle_graph):
     with pytest.raises(ggnn.GgnnError):
         g.query(dev(queries[:4]), 10, 10, 0.3, visited_cap=100, max_iter=200)
     with pytest.raises(ggnn.GgnnError):
-        g.query(dev(queries[:4]), 10, 4000, 0.3, pq_cap=4000, visited_cap=4000)  # over the LDS budget
+        g.query(dev(queries[:4]), 10, 4000, 0.3, pq_cap=4000, visited_cap=20000)  # over the LDS budget
     bad = og.edges(0).copy()
     bad[5, 3] = bad[5, 2]
     with pytest.raises(ggnn.GgnnError):
