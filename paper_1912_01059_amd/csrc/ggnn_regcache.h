@@ -75,13 +75,20 @@ struct RegCacheT {
   uint32_t pops, evals, gathers;
 
   static constexpr int kListedBuckets = 8192;
-  // Hash slots: room for every visited id plus at least 128 rejected ids at a load of one half;
-  // 1024 slots (4 KB) when that suffices, so that six wavefronts per SIMD fit into the LDS (fewer slots
-  // remember fewer rejected points and cost more than they save).
+  // Hash slots (a power of two).  Up to 384 iterations: 1024 slots (4 KB, which six wavefronts per SIMD
+  // can afford), filled to at most one half by the visited ids and at least 128 rejected ids (fewer
+  // slots remember fewer rejected points and cost more than they save).  Beyond, LDS decides how many
+  // wavefronts a compute unit holds, and the table may fill to three quarters.
   __host__ __device__ static int hash_slots(int max_iter) {
     int h = 1024;
-    while (h < 2 * max_iter + 256) h <<= 1;
+    if (2 * max_iter + 256 <= h) return h;
+    while (3 * h < 4 * (max_iter + 128)) h <<= 1;
     return h;
+  }
+  // visited ids plus rejected ids the table may hold
+  __host__ __device__ static int hash_fill(int max_iter) {
+    const int h = hash_slots(max_iter);
+    return 2 * max_iter + 256 <= h ? h / 2 : h / 4 * 3;
   }
   // the staging area of Transform ((2 NB + 2) x 64 keys) shares its memory with the hash table,
   // which Transform empties anyway
@@ -105,7 +112,7 @@ struct RegCacheT {
     surv_row = surv_id + 64;
     surv_d = (float*)(surv_row + 64);
     listed_bits = (uint32_t*)(surv_d + 64);
-    rej_cap = H / 2 - sp.max_iter;
+    rej_cap = hash_fill(sp.max_iter) - sp.max_iter;
   }
   // ---- which ids may be in best or prioq: one bit per bucket (a zero bit rules a proposal out)
   // one multiplicative hash serves both tables: its top bits index the visited / rejected table,
