@@ -197,6 +197,16 @@ int ggnn_set_cache_mode(int32_t mode);
  * value above every batch size turns the two-launch path off.  Process-wide. */
 int ggnn_set_split_threshold(int64_t min_queries);
 
+/* Where user queries keep their visited set.  By default (min_iter = 0) in LDS, except for batches
+ * with an iteration limit (max_iter) of 1024 and more that are larger than the number of wavefronts
+ * the GPU holds at once with such a table in LDS: those use one table per query in global memory
+ * (taken from the stream's memory pool for the duration of the call), which is slower to probe but
+ * leaves room for six wavefronts per SIMD.  min_iter > 0: global memory for every batch whose limit
+ * is at least min_iter; min_iter < 0: always LDS.  Results and counters do not depend on it (Alg. 2
+ * only asks that visited be exact).  Process-wide, not thread-safe against concurrent queries.
+ * Returns GGNN_OK. */
+int ggnn_set_global_visited_threshold(int32_t min_iter);
+
 /* Measurement aid (not part of the method): gathers rows ids_dev[0..n_ids) (each in [0, n_rows), not
  * checked) of rows_dev (row_bytes per row, multiple of 16, <= 512) with the search kernels' access
  * pattern, rows_per_wave rows per wavefront, and writes one word per lane to out_dev

@@ -46,7 +46,7 @@ EXPORTS = [
     "ggnn_build", "ggnn_build_ex", "ggnn_graph_create", "ggnn_select", "ggnn_merge", "ggnn_sym",
     "ggnn_build_steps", "ggnn_build_get_times", "ggnn_query", "ggnn_query_ex", "ggnn_query_from", "ggnn_graph_info",
     "ggnn_graph_export", "ggnn_graph_import", "ggnn_graph_export_dnn", "ggnn_graph_import_dnn",
-    "ggnn_graph_export_inv_count", "ggnn_set_cache_mode", "ggnn_set_split_threshold", "ggnn_gather_probe", "ggnn_merge_shards", "ggnn_free", "ggnn_last_error",
+    "ggnn_graph_export_inv_count", "ggnn_set_cache_mode", "ggnn_set_split_threshold", "ggnn_set_global_visited_threshold", "ggnn_gather_probe", "ggnn_merge_shards", "ggnn_free", "ggnn_last_error",
 ]
 
 
@@ -78,6 +78,7 @@ def lib():
         L.ggnn_graph_export_inv_count.argtypes = [vp, i32, vp]
         L.ggnn_set_cache_mode.argtypes = [i32]
         L.ggnn_set_split_threshold.argtypes = [i64]
+        L.ggnn_set_global_visited_threshold.argtypes = [C.c_int32]
         L.ggnn_gather_probe.argtypes = [vp, i64, i32, vp, i64, i32, vp, vp]
         L.ggnn_merge_shards.argtypes = [i32, i64, i32, vp, vp, vp, vp, vp, vp, i32]
         L.ggnn_free.argtypes = [vp]
@@ -90,6 +91,11 @@ def lib():
 def set_cache_mode(mode: int) -> None:
     """0: best / prioq in registers when they fit (default); 1: always in LDS."""
     _check(lib().ggnn_set_cache_mode(mode))
+
+
+def set_global_visited_threshold(min_iter: int) -> None:
+    """ggnn_set_global_visited_threshold: iteration limit from which user queries keep visited in global memory."""
+    _check(lib().ggnn_set_global_visited_threshold(min_iter))
 
 
 def set_split_threshold(min_queries: int) -> None:

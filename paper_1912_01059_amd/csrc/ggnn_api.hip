@@ -150,7 +150,7 @@ int make_search_params(int B, int P, int V, int max_iter, float tau, float dnn, 
   sp->H = next_pow2(2 * (max_iter > 0 ? max_iter : 1));
   if (sp->H < 64) sp->H = 64;
   sp->tau = tau; sp->dnn = dnn;
-  sp->start = nullptr; sp->n_start = 0;
+  sp->start = nullptr; sp->n_start = 0; sp->vis = nullptr;
   const int slots = register_slots(*sp, user_query);
   const size_t need = slots == 1 ? RegCache::lds_bytes(*sp) : slots == 2 ? RegCache2::lds_bytes(*sp) : LdsCache::lds_bytes(*sp);
   if (need > kMaxLds)
@@ -172,12 +172,33 @@ hipError_t launch_query_whole(const GraphDev& G, int dtype, int metric, const vo
 // ordered by region (see SplitBufs); smaller ones gain nothing from it.
 constexpr int64_t kSplitMinQueries = 24576;
 int64_t g_split_min_queries = kSplitMinQueries;
+constexpr int32_t kVisGlobalMinIter = 1024;  // iteration limit from which user queries keep visited in global memory
+int32_t g_vis_global_min_iter = kVisGlobalMinIter;
+bool g_vis_global_forced = false;  // set through ggnn_set_global_visited_threshold: applies whatever the batch size
 
 hipError_t launch_query(const GraphDev& G, int dtype, int metric, const void* queries, int64_t Q, int k,
                         const SearchParams& sp, int every_layer, int32_t* ids, float* dists, uint32_t* counters,
                         hipStream_t stream) {
   SplitBufs sb = {};
   const int slots = register_slots(sp, true);
+  // wavefronts the GPU holds at once when the visited table is in LDS (256 compute units, at most 24
+  // wavefronts each): a batch that fits gains nothing from a table in global memory, which is slower to probe
+  const size_t lds_table = slots == 2 ? RegCache2::lds_bytes(sp) : RegCache::lds_bytes(sp);
+  const int64_t resident = 256 * (int64_t)(kMaxLds / lds_table < 24 ? kMaxLds / lds_table : 24);
+  if (slots >= 1 && g_vis_global_min_iter > 0 && sp.max_iter >= g_vis_global_min_iter &&
+      (Q > resident || g_vis_global_forced)) {
+    // long searches: one visited table per query in global memory, from the stream's memory pool
+    const size_t bytes = (size_t)Q * (size_t)RegCacheGV::vis_slots(sp.max_iter) * sizeof(int32_t);
+    int32_t* vis = nullptr;
+    if (hipMallocAsync((void**)&vis, bytes, stream) == hipSuccess) {
+      SearchParams spv = sp;
+      spv.vis = vis;
+      const hipError_t e = launch_query_gv(slots, G, dtype, metric, queries, Q, k, spv, every_layer, ids, dists, counters, stream);
+      const hipError_t f = hipFreeAsync(vis, stream);
+      return e != hipSuccess ? e : f;
+    }
+    (void)hipGetLastError();  // no workspace: the table stays in LDS
+  }
   const bool split = every_layer && G.L >= 3 && !sp.start && slots >= 1 && Q >= g_split_min_queries;
   if (!split) return launch_query_whole(G, dtype, metric, queries, Q, k, sp, every_layer, ids, dists, counters, stream);
   // workspace from the stream's memory pool: lists, counters, keys, order, bins
@@ -310,6 +331,12 @@ int ggnn_set_cache_mode(int32_t mode) {
 int ggnn_set_split_threshold(int64_t min_queries) {
   if (min_queries < 0) return fail(GGNN_ERR_INVALID, "min_queries = %lld is negative", (long long)min_queries);
   g_split_min_queries = min_queries == 0 ? kSplitMinQueries : min_queries;
+  return GGNN_OK;
+}
+
+int ggnn_set_global_visited_threshold(int32_t min_iter) {
+  g_vis_global_min_iter = min_iter == 0 ? kVisGlobalMinIter : min_iter;  // negative: never
+  g_vis_global_forced = min_iter > 0;
   return GGNN_OK;
 }
 

@@ -38,6 +38,7 @@ struct SearchParams {
   float tau, dnn;
   const int32_t* start;  // user queries only: explicit start points on the bottom layer, or null
   int32_t n_start;
+  int32_t* vis;          // user queries only: per-query visited tables in global memory, or null
 };
 
 // A large batch of user queries is answered in two launches: the upper layers first, then the bottom
@@ -555,7 +556,7 @@ struct LdsCache {
   static constexpr bool kInRegisters = false;
   Cache c;
   __host__ __device__ static size_t lds_bytes(const SearchParams& sp) { return cache_lds_bytes(sp.B, sp.P, sp.H); }
-  __device__ void bind(unsigned char* lds, const SearchParams& sp) { cache_bind(c, lds, sp); }
+  __device__ void bind(unsigned char* lds, const SearchParams& sp, int64_t) { cache_bind(c, lds, sp); }
   __device__ void init() { cache_init(c); }
   __device__ void set_radius(float r) { c.radius = r; }
   template <int DT, int NCH, int METRIC, int PASSES>

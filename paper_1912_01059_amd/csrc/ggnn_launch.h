@@ -45,6 +45,11 @@ hipError_t launch_query_reg2(const GraphDev& G, int dtype, int metric, const voi
 hipError_t launch_query_split(int slots, const GraphDev& G, int dtype, int metric, const void* queries, int64_t Q, int k,
                               const SearchParams& sp, int32_t* ids, float* dists, uint32_t* counters,
                               const SplitBufs& sb, hipStream_t stream);
+// ggnn_search_gv.hip: user queries with the visited ids in global memory (sp.vis: Q tables of
+// RegCacheGV::vis_slots(sp.max_iter) words); slots as above
+hipError_t launch_query_gv(int slots, const GraphDev& G, int dtype, int metric, const void* queries, int64_t Q, int k,
+                           const SearchParams& sp, int every_layer, int32_t* ids, float* dists, uint32_t* counters,
+                           hipStream_t stream);
 GGNN_SEARCH_LAUNCHERS(_lds)
 #undef GGNN_SEARCH_LAUNCHERS
 

@@ -51,7 +51,10 @@ __device__ unsigned long long g_phase_cycles[16];
 #define GGNN_TICK(i)
 #endif
 
-template <int NB>
+// GV: the visited ids live in a table in global memory (one per query, handed in through
+// SearchParams::vis) instead of LDS, which then holds the rejected ids only: for searches of a thousand
+// iterations and more the LDS table is what limits the wavefronts a compute unit holds.
+template <int NB, bool GV = false>
 struct RegCacheT {
   static constexpr bool kInRegisters = true;
   static constexpr int kBestSlots = NB;
@@ -67,7 +70,8 @@ struct RegCacheT {
   int32_t iter, max_iter;
   float tau, dnn, radius, d1, dk, thr_now;
   u64 last_best;                 // key of best[B-1]
-  int32_t* hash; int32_t hmask, hshift;  // LDS: visited ids, and rejected ids with the top bit set
+  int32_t* hash; int32_t hmask, hshift;  // LDS: visited ids (unless GV), and rejected ids with the top bit set
+  int32_t* vis; int32_t vmask, vshift;   // GV: visited ids in global memory
   uint32_t* listed_bits;         // LDS: kListedBuckets bits
   int32_t nrej, rej_cap;
   u64* stage;                    // LDS: 4 x 64 keys for Transform
@@ -81,14 +85,20 @@ struct RegCacheT {
   // wavefronts a compute unit holds, and the table may fill to three quarters.
   __host__ __device__ static int hash_slots(int max_iter) {
     int h = 1024;
-    if (2 * max_iter + 256 <= h) return h;
+    if (GV || 2 * max_iter + 256 <= h) return h;
     while (3 * h < 4 * (max_iter + 128)) h <<= 1;
     return h;
   }
   // visited ids plus rejected ids the table may hold
   __host__ __device__ static int hash_fill(int max_iter) {
     const int h = hash_slots(max_iter);
-    return 2 * max_iter + 256 <= h ? h / 2 : h / 4 * 3;
+    return (GV || 2 * max_iter + 256 <= h) ? h / 2 : h / 4 * 3;
+  }
+  // GV: slots of the visited table in global memory (a power of two, filled to at most one half)
+  __host__ __device__ static int vis_slots(int max_iter) {
+    int h = 64;
+    while (h < 2 * max_iter) h <<= 1;
+    return h;
   }
   // the staging area of Transform ((2 NB + 2) x 64 keys) shares its memory with the hash table,
   // which Transform empties anyway
@@ -101,8 +111,14 @@ struct RegCacheT {
     return hash_bytes(sp) + 3 * 64 * 4 + kListedBuckets / 8;
   }
 
-  __device__ void bind(unsigned char* lds, const SearchParams& sp) {
+  __device__ void bind(unsigned char* lds, const SearchParams& sp, int64_t query) {
     B = sp.B; P = sp.P; max_iter = sp.max_iter; tau = sp.tau; dnn = sp.dnn;
+    if (GV) {
+      const int VS = vis_slots(sp.max_iter);
+      vis = sp.vis + (size_t)query * (size_t)VS;
+      vmask = VS - 1;
+      vshift = 32 - (31 - __builtin_clz((unsigned)VS));
+    }
     const int H = hash_slots(sp.max_iter);
     stage = (u64*)lds;
     hash = (int32_t*)lds;
@@ -112,7 +128,7 @@ struct RegCacheT {
     surv_row = surv_id + 64;
     surv_d = (float*)(surv_row + 64);
     listed_bits = (uint32_t*)(surv_d + 64);
-    rej_cap = hash_fill(sp.max_iter) - sp.max_iter;
+    rej_cap = GV ? hash_fill(sp.max_iter) : hash_fill(sp.max_iter) - sp.max_iter;
   }
   // ---- which ids may be in best or prioq: one bit per bucket (a zero bit rules a proposal out)
   // one multiplicative hash serves both tables: its top bits index the visited / rejected table,
@@ -130,9 +146,22 @@ struct RegCacheT {
     const uint32_t h = listed_bucket(id);
     return (listed_bits[h >> 5] >> (h & 31)) & 1u;
   }
+  // The global table is written and read by this wavefront only: relaxed accesses of work-group scope,
+  // and a work-group fence between a write and the reads that must see it.
+  __device__ __forceinline__ static int32_t vis_load(const int32_t* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+  }
+  __device__ __forceinline__ static void vis_store(int32_t* p, int32_t v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+  }
+  __device__ __forceinline__ static void vis_fence() { __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup"); }
   __device__ void clear_hash() {
     for (int i = lane_id(); i <= hmask; i += kWave) hash[i] = -1;
     nrej = 0;
+    if (GV) {
+      for (int i = lane_id(); i <= vmask; i += kWave) vis_store(&vis[i], -1);
+      vis_fence();
+    }
     wave_sync();
   }
   // Alg. 2 Init
@@ -149,15 +178,42 @@ struct RegCacheT {
 
   // 0: unknown, 1: visited, 2: evaluated before and rejected
   __device__ int probe(int32_t id) const {
-    uint32_t h = slot_of(id);
-    int32_t v;
-    while ((v = hash[h]) != -1) {
-      if ((v & 0x7FFFFFFF) == id) return (v < 0) ? 2 : 1;
-      h = (h + 1) & (uint32_t)hmask;
+    if constexpr (GV) {
+      // the first probe of the global table is under way while the LDS table (rejected ids) is searched
+      uint32_t gh = hash_of(id) >> vshift;
+      int32_t gv = vis_load(&vis[gh]);
+      int kind = 0;
+      uint32_t h = slot_of(id);
+      int32_t v;
+      while ((v = hash[h]) != -1) {
+        if ((v & 0x7FFFFFFF) == id) { kind = 2; break; }
+        h = (h + 1) & (uint32_t)hmask;
+      }
+      while (gv != -1) {
+        if (gv == id) return 1;
+        gh = (gh + 1) & (uint32_t)vmask;
+        gv = vis_load(&vis[gh]);
+      }
+      return kind;
+    } else {
+      uint32_t h = slot_of(id);
+      int32_t v;
+      while ((v = hash[h]) != -1) {
+        if ((v & 0x7FFFFFFF) == id) return (v < 0) ? 2 : 1;
+        h = (h + 1) & (uint32_t)hmask;
+      }
+      return 0;
     }
-    return 0;
   }
   __device__ void insert_visited(int32_t id) {  // uniform call
+    if (GV) {
+      if (lane_id() == 0) {
+        uint32_t h = hash_of(id) >> vshift;
+        while (vis_load(&vis[h]) != -1) h = (h + 1) & (uint32_t)vmask;
+        vis_store(&vis[h], id);
+      }
+      return;  // the fence before the next probes orders this write before them
+    }
     if (lane_id() == 0) {
       uint32_t h = slot_of(id);
       while (hash[h] != -1) h = (h + 1) & (uint32_t)hmask;
@@ -338,6 +394,7 @@ struct RegCacheT {
     GGNN_TICK(1);  // adjacency row arrives
     const bool bit = maybe_listed(p);  // read alongside the first probe, not after the last (any p indexes the map)
     bool seen_rejected = false;
+    if constexpr (GV) vis_fence();  // the popped id's entry is in the table (the adjacency row was awaited anyway)
     if (alive) {
       const int kind = probe(p);
       alive = kind == 0;
@@ -505,5 +562,7 @@ struct RegCacheT {
 
 using RegCache = RegCacheT<1>;   // best of at most 64 entries
 using RegCache2 = RegCacheT<2>;  // best of at most 128 entries
+using RegCacheGV = RegCacheT<1, true>;   // the same with the visited ids in global memory (user queries)
+using RegCache2GV = RegCacheT<2, true>;
 
 }  // namespace ggnn

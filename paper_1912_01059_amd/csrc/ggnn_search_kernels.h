@@ -68,7 +68,7 @@ __device__ __forceinline__ void query_body(const GraphDev& G, const uint8_t* __r
     qi = sb.order[i];
   }
   C c;
-  c.bind(lds, sp);
+  c.bind(lds, sp, qi);
   c.init();
   QueryRegs<DT, NCH> q;
   load_query<DT, NCH>(q, queries + (size_t)qi * (size_t)G.row_bytes, G.nchunks);
@@ -137,7 +137,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(SearchWav
   const int lane = lane_id();
   const int64_t z = blockIdx.x;
   C c;
-  c.bind(lds, sp);
+  c.bind(lds, sp, z);
   c.init();
   const int32_t zrow = (l_m == 0) ? (int32_t)z : G.to_base[l_m][z];
   QueryRegs<DT, NCH> q;
@@ -196,7 +196,7 @@ __global__ __launch_bounds__(kWave) void sym_search_kernel(GraphDev G, int layer
     if (__ballot(hit)) return;
   }
   C c;
-  c.bind(lds, sp);
+  c.bind(lds, sp, z);
   c.init();
   const int32_t zrow = (layer == 0) ? (int32_t)z : G.to_base[layer][z];
   const int32_t xrow = (layer == 0) ? x : G.to_base[layer][x];

@@ -396,3 +396,70 @@ def test_two_launch_path_matches_one_launch_and_oracle(ggnn, R, sift10k, sift10k
         rids, rd, rcnt = og.query(q, k, beam, tau, pq_cap=P, every_layer=True, counters=True)
         assert_same_results(ids2, d2, rids, rd)
         check_counters(c2, rcnt)
+
+
+# ------------------------------------------------------------------------------ visited set in global memory
+
+def test_global_visited_table_matches_lds_table_and_oracle(ggnn, R, sift10k, sift10k_oracle_graph):
+    """Long searches keep the visited ids in a per-query table in global memory instead of LDS.  Forced
+    here for short ones too: results and the method's counters (pops, distance evaluations) must be
+    those of the LDS table and of the oracle, in both descent modes, for both best-list widths, with
+    explicit start points, and on cosine and uint8 data."""
+    import ggnn_inputs
+    base, queries, cfg = sift10k
+    og = sift10k_oracle_graph
+    g = to_gpu_graph(ggnn, og, dev(base))
+    rng = np.random.default_rng(5)
+    cases = [(500, 10, 10, 0.3, 64, 384, True), (300, 10, 100, 0.2, 64, 200, False), (64, 24, 24, 1.0, 32, 1500, True),
+             (5, 1, 1, 0.0, 64, 1, True), (200, 100, 128, 0.4, 64, 3000, True)]
+    for Q, k, beam, tau, P, V, every in cases:
+        q = queries[rng.integers(0, len(queries), Q)].copy()
+        kw = dict(pq_cap=P, visited_cap=V, max_iter=V, every_layer=every, counters=True)
+        ggnn.set_global_visited_threshold(-1)
+        try:
+            ids1, d1, c1 = g.query(dev(q), k, beam, tau, **kw)
+            ggnn.set_global_visited_threshold(1)
+            ids2, d2, c2 = g.query(dev(q), k, beam, tau, **kw)
+        finally:
+            ggnn.set_global_visited_threshold(0)
+        assert torch.equal(ids1, ids2) and torch.equal(d1.view(torch.int32), d2.view(torch.int32))
+        assert torch.equal(c1[:, :2], c2[:, :2])
+        rids, rd, rcnt = og.query(q, k, beam, tau, pq_cap=P, visited_cap=V, max_iter=V, every_layer=every, counters=True)
+        assert_same_results(ids2, d2, rids, rd)
+        check_counters(c2, rcnt)
+    # explicit start points on the bottom layer
+    starts = np.arange(0, 3200, 100, dtype=np.int32)
+    ggnn.set_global_visited_threshold(1)
+    try:
+        ids, d, c = g.query(dev(queries[:200]), 10, 16, 0.5, visited_cap=256, counters=True, start_ids=dev(starts))
+    finally:
+        ggnn.set_global_visited_threshold(0)
+    rids, rd, rcnt = og.query(queries[:200], 10, 16, 0.5, visited_cap=256, counters=True, start_ids=starts)
+    assert_same_results(ids, d, rids, rd)
+    check_counters(c, rcnt)
+    # other element types and metrics
+    for name, n, nq in (("glove1m", 4000, 200), ("deep1m", 4000, 200)):
+        b2, q2, c2cfg = ggnn_inputs.make(name, n=n, q=nq)
+        metric_o = R.COSINE if c2cfg["metric"] == "cosine" else R.L2
+        og2 = R.Graph(b2, c2cfg["K"], 3, metric=metric_o, seed=7).build(R.default_params(visited_cap=96, max_iter=96))
+        g2 = to_gpu_graph(ggnn, og2, dev(b2))
+        ggnn.set_global_visited_threshold(1)
+        try:
+            ids, d, c = g2.query(dev(q2), 10, 10, 0.4, visited_cap=700, every_layer=True, counters=True)
+        finally:
+            ggnn.set_global_visited_threshold(0)
+        rids, rd, rcnt = og2.query(q2, 10, 10, 0.4, visited_cap=700, every_layer=True, counters=True)
+        assert_same_results(ids, d, rids, rd)
+        check_counters(c, rcnt)
+    b3 = np.random.default_rng(9).integers(0, 256, (3000, 64)).astype(np.uint8)
+    q3 = np.random.default_rng(10).integers(0, 256, (150, 64)).astype(np.uint8)
+    og3 = R.Graph(b3, 24, 3, seed=7).build(R.default_params(visited_cap=96, max_iter=96))
+    g3 = to_gpu_graph(ggnn, og3, dev(b3))
+    ggnn.set_global_visited_threshold(1)
+    try:
+        ids, d, c = g3.query(dev(q3), 10, 10, 0.6, visited_cap=600, every_layer=True, counters=True)
+    finally:
+        ggnn.set_global_visited_threshold(0)
+    rids, rd, rcnt = og3.query(q3, 10, 10, 0.6, visited_cap=600, every_layer=True, counters=True)
+    assert_same_results(ids, d, rids, rd)
+    check_counters(c, rcnt)
