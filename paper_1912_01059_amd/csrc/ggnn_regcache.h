@@ -8,8 +8,8 @@
 // result (rejected entries may be left out when the table fills up; visited entries never are).
 // Whether a proposal already sits in best or prioq is decided exactly by comparing it with the
 // entry every lane holds; a bit map in LDS (one bit per hash bucket, set when an id of that bucket
-// enters a list and cleared only when the layer changes) first rules out the many proposals
-// that cannot be listed.
+// enters a list, rebuilt from the lists every few iterations and when the layer changes) first rules
+// out the many proposals that cannot be listed.
 #pragma once
 #include "ggnn_device.h"
 
@@ -303,7 +303,33 @@ struct RegCacheT {
     pops++;
     return key_id(head);
   }
-  __device__ void mark_visited(int32_t id) { insert_visited(id); }
+  __device__ void mark_visited(int32_t id) {
+    insert_visited(id);
+    if ((iter & (kRelistEvery - 1)) == 0) relist();
+  }
+  // The bit map only ever gains bits while a layer is searched, and most ids that enter prioq fall off
+  // its end again: every kRelistEvery iterations it is rebuilt from the two lists as they stand, so that
+  // a set bit keeps meaning "probably listed" (few exact membership tests) in long searches too.
+  static constexpr int kRelistEvery = 4;
+  __device__ void relist() {
+    listed_clear();
+    mark_lists();
+    wave_sync();
+  }
+  __device__ __forceinline__ void mark_lists() {
+    const int lane = lane_id();
+#pragma unroll
+    for (int e = 0; e < NB; e++) {
+      if (e * kWave + lane < nb) {
+        const uint32_t h = listed_bucket(key_id(best[e]));
+        atomicOr(&listed_bits[h >> 5], 1u << (h & 31));
+      }
+    }
+    if (lane < np) {
+      const uint32_t h = listed_bucket(key_id(pq));
+      atomicOr(&listed_bits[h >> 5], 1u << (h & 31));
+    }
+  }
   __device__ int32_t next_head() const { return np > 0 ? key_id(read_lane_u64(pq, 0)) : -1; }
   __device__ int32_t pop() {
     const int32_t id = pop_head();
@@ -366,17 +392,7 @@ struct RegCacheT {
     iter = 0;
     if (nb > 0) refresh_bounds();
     listed_clear();
-#pragma unroll
-    for (int e = 0; e < NB; e++) {
-      if (e * kWave + lane < nb) {
-        const uint32_t h = listed_bucket(key_id(best[e]));
-        atomicOr(&listed_bits[h >> 5], 1u << (h & 31));
-      }
-    }
-    if (lane < np) {
-      const uint32_t h = listed_bucket(key_id(pq));
-      atomicOr(&listed_bits[h >> 5], 1u << (h & 31));
-    }
+    mark_lists();
     clear_hash();
   }
 
