@@ -140,7 +140,11 @@ int ggnn_query(const ggnn_graph* g, const void* queries_dev, int64_t Q, int32_t 
  * optional Q x 4 uint32 (device), per query: pops (iterations of Alg. 1); distance evaluations of
  * the method (Alg. 2 Fetch: a point counts again each time it is proposed while unknown to the
  * cache); base rows actually gathered (fewer: re-evaluations of rejected points are skipped); 0.
- * asynchronous != 0 returns right after the launch (no synchronisation). */
+ * asynchronous != 0 returns right after the launch (no synchronisation).
+ * Memory: a call allocates nothing, except that large batches (ggnn_set_split_threshold) and large
+ * batches of long searches (ggnn_set_global_visited_threshold) take a workspace from the stream's memory
+ * pool (hipMallocAsync / hipFreeAsync on `stream`) for the duration of the call; if the pool cannot
+ * provide it, the call proceeds without it. */
 int ggnn_query_ex(const ggnn_graph* g, const void* queries_dev, int64_t Q, int32_t k, int32_t beam, float slack,
                   int32_t pq_cap, int32_t visited_cap, int32_t max_iter, int32_t every_layer, void* stream,
                   int32_t* ids_dev, float* dists_dev, uint32_t* counters_dev, int32_t asynchronous);
