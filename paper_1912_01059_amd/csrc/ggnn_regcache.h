@@ -80,9 +80,10 @@ struct RegCacheT {
 
   static constexpr int kListedBuckets = 8192;
   // Hash slots (a power of two).  Up to 384 iterations: 1024 slots (4 KB, which six wavefronts per SIMD
-  // can afford), filled to at most one half by the visited ids and at least 128 rejected ids (fewer
-  // slots remember fewer rejected points and cost more than they save).  Beyond, LDS decides how many
-  // wavefronts a compute unit holds, and the table may fill to three quarters.
+  // can afford), filled to three eighths (or by the visited ids plus 128 rejected ids, if that is more):
+  // probing a fuller table costs more than the rejected ids it remembers save, an emptier one gathers
+  // too many rows again (measured: 1/4, 3/8, 1/2, 3/4).  Beyond, LDS decides how many wavefronts a
+  // compute unit holds, and the table may fill to three quarters.
   __host__ __device__ static int hash_slots(int max_iter) {
     int h = 1024;
     if (GV || 2 * max_iter + 256 <= h) return h;
@@ -92,7 +93,9 @@ struct RegCacheT {
   // visited ids plus rejected ids the table may hold
   __host__ __device__ static int hash_fill(int max_iter) {
     const int h = hash_slots(max_iter);
-    return (GV || 2 * max_iter + 256 <= h) ? h / 2 : h / 4 * 3;
+    if (GV) return h / 2;
+    if (2 * max_iter + 256 <= h) return (h * 3 / 8 > max_iter + 128) ? h * 3 / 8 : max_iter + 128;
+    return h / 4 * 3;
   }
   // GV: slots of the visited table in global memory (a power of two, filled to at most one half)
   __host__ __device__ static int vis_slots(int max_iter) {
