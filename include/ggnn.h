@@ -202,7 +202,7 @@ int ggnn_set_cache_mode(int32_t mode);
 int ggnn_set_split_threshold(int64_t min_queries);
 
 /* Where user queries keep their visited set.  By default (min_iter = 0) in LDS, except for batches
- * with an iteration limit (max_iter) of 1024 and more that are larger than the number of wavefronts
+ * with an iteration limit (max_iter) of 1100 and more that are larger than the number of wavefronts
  * the GPU holds at once with such a table in LDS: those use one table per query in global memory
  * (taken from the stream's memory pool for the duration of the call), which is slower to probe but
  * leaves room for six wavefronts per SIMD.  min_iter > 0: global memory for every batch whose limit

@@ -163,6 +163,9 @@ hipError_t launch_query_whole(const GraphDev& G, int dtype, int metric, const vo
                               const SearchParams& sp, int every_layer, int32_t* ids, float* dists, uint32_t* counters,
                               hipStream_t stream) {
   const int slots = register_slots(sp, true);
+  // beyond 384 iterations a power-of-two table would be larger than 1024 slots: size it to the limit
+  if (slots >= 1 && 2 * sp.max_iter + 256 > 1024)
+    return launch_query_any(slots, G, dtype, metric, queries, Q, k, sp, every_layer, ids, dists, counters, stream);
   if (slots == 1) return launch_query_reg(G, dtype, metric, queries, Q, k, sp, every_layer, ids, dists, counters, stream);
   if (slots == 2) return launch_query_reg2(G, dtype, metric, queries, Q, k, sp, every_layer, ids, dists, counters, stream);
   return launch_query_lds(G, dtype, metric, queries, Q, k, sp, every_layer, ids, dists, counters, stream);
@@ -172,7 +175,7 @@ hipError_t launch_query_whole(const GraphDev& G, int dtype, int metric, const vo
 // ordered by region (see SplitBufs); smaller ones gain nothing from it.
 constexpr int64_t kSplitMinQueries = 24576;
 int64_t g_split_min_queries = kSplitMinQueries;
-constexpr int32_t kVisGlobalMinIter = 1024;  // iteration limit from which user queries keep visited in global memory
+constexpr int32_t kVisGlobalMinIter = 1100;  // iteration limit from which user queries keep visited in global memory
 int32_t g_vis_global_min_iter = kVisGlobalMinIter;
 bool g_vis_global_forced = false;  // set through ggnn_set_global_visited_threshold: applies whatever the batch size
 
@@ -183,7 +186,7 @@ hipError_t launch_query(const GraphDev& G, int dtype, int metric, const void* qu
   const int slots = register_slots(sp, true);
   // wavefronts the GPU holds at once when the visited table is in LDS (256 compute units, at most 24
   // wavefronts each): a batch that fits gains nothing from a table in global memory, which is slower to probe
-  const size_t lds_table = slots == 2 ? RegCache2::lds_bytes(sp) : RegCache::lds_bytes(sp);
+  const size_t lds_table = slots == 2 ? RegCache2Any::lds_bytes(sp) : RegCacheAny::lds_bytes(sp);
   const int64_t resident = 256 * (int64_t)(kMaxLds / lds_table < 24 ? kMaxLds / lds_table : 24);
   if (slots >= 1 && g_vis_global_min_iter > 0 && sp.max_iter >= g_vis_global_min_iter &&
       (Q > resident || g_vis_global_forced)) {

@@ -50,6 +50,10 @@ hipError_t launch_query_split(int slots, const GraphDev& G, int dtype, int metri
 hipError_t launch_query_gv(int slots, const GraphDev& G, int dtype, int metric, const void* queries, int64_t Q, int k,
                            const SearchParams& sp, int every_layer, int32_t* ids, float* dists, uint32_t* counters,
                            hipStream_t stream);
+// ggnn_search_any.hip: user queries with an LDS table of any multiple of 64 slots; slots as above
+hipError_t launch_query_any(int slots, const GraphDev& G, int dtype, int metric, const void* queries, int64_t Q, int k,
+                            const SearchParams& sp, int every_layer, int32_t* ids, float* dists, uint32_t* counters,
+                            hipStream_t stream);
 GGNN_SEARCH_LAUNCHERS(_lds)
 #undef GGNN_SEARCH_LAUNCHERS
 

@@ -54,7 +54,9 @@ __device__ unsigned long long g_phase_cycles[16];
 // GV: the visited ids live in a table in global memory (one per query, handed in through
 // SearchParams::vis) instead of LDS, which then holds the rejected ids only: for searches of a thousand
 // iterations and more the LDS table is what limits the wavefronts a compute unit holds.
-template <int NB, bool GV = false>
+// ANY: the LDS table may have any multiple of 64 slots (searches of a few hundred to a thousand
+// iterations, where the step to the next power of two would cost a wavefront per SIMD).
+template <int NB, bool GV = false, bool ANY = false>
 struct RegCacheT {
   static constexpr bool kInRegisters = true;
   static constexpr int kBestSlots = NB;
@@ -87,6 +89,7 @@ struct RegCacheT {
   __host__ __device__ static int hash_slots(int max_iter) {
     int h = 1024;
     if (GV || 2 * max_iter + 256 <= h) return h;
+    if (ANY) return (2 * max_iter + 256 + 63) / 64 * 64;
     while (3 * h < 4 * (max_iter + 128)) h <<= 1;
     return h;
   }
@@ -95,6 +98,7 @@ struct RegCacheT {
     const int h = hash_slots(max_iter);
     if (GV) return h / 2;
     if (2 * max_iter + 256 <= h) return (h * 3 / 8 > max_iter + 128) ? h * 3 / 8 : max_iter + 128;
+    if (ANY) return h / 2;
     return h / 4 * 3;
   }
   // GV: slots of the visited table in global memory (a power of two, filled to at most one half)
@@ -140,7 +144,14 @@ struct RegCacheT {
   __device__ __forceinline__ static uint32_t listed_bucket(int32_t id) {
     return (hash_of(id) >> 6) & (uint32_t)(kListedBuckets - 1);
   }
-  __device__ __forceinline__ uint32_t slot_of(int32_t id) const { return hash_of(id) >> hshift; }
+  __device__ __forceinline__ uint32_t slot_of(int32_t id) const {
+    if constexpr (ANY) return __umul24(hash_of(id) >> 16, (uint32_t)hmask + 1u) >> 16;  // top 16 bits x slots
+    else return hash_of(id) >> hshift;
+  }
+  __device__ __forceinline__ uint32_t next_slot(uint32_t h) const {
+    if constexpr (ANY) return h == (uint32_t)hmask ? 0u : h + 1;
+    else return (h + 1) & (uint32_t)hmask;
+  }
   __device__ void listed_clear() {
     for (int i = lane_id(); i < kListedBuckets / 32; i += kWave) listed_bits[i] = 0;
     wave_sync();
@@ -190,7 +201,7 @@ struct RegCacheT {
       int32_t v;
       while ((v = hash[h]) != -1) {
         if ((v & 0x7FFFFFFF) == id) { kind = 2; break; }
-        h = (h + 1) & (uint32_t)hmask;
+        h = next_slot(h);
       }
       while (gv != -1) {
         if (gv == id) return 1;
@@ -203,7 +214,7 @@ struct RegCacheT {
       int32_t v;
       while ((v = hash[h]) != -1) {
         if ((v & 0x7FFFFFFF) == id) return (v < 0) ? 2 : 1;
-        h = (h + 1) & (uint32_t)hmask;
+        h = next_slot(h);
       }
       return 0;
     }
@@ -219,7 +230,7 @@ struct RegCacheT {
     }
     if (lane_id() == 0) {
       uint32_t h = slot_of(id);
-      while (hash[h] != -1) h = (h + 1) & (uint32_t)hmask;
+      while (hash[h] != -1) h = next_slot(h);
       hash[h] = id;
     }
     wave_sync();
@@ -230,7 +241,7 @@ struct RegCacheT {
     nrej += cnt;
     if (mine) {
       uint32_t h = slot_of(id);
-      while (atomicCAS(&hash[h], -1, (int32_t)((uint32_t)id | 0x80000000u)) != -1) h = (h + 1) & (uint32_t)hmask;
+      while (atomicCAS(&hash[h], -1, (int32_t)((uint32_t)id | 0x80000000u)) != -1) h = next_slot(h);
     }
     wave_sync();
   }
@@ -583,5 +594,7 @@ using RegCache = RegCacheT<1>;   // best of at most 64 entries
 using RegCache2 = RegCacheT<2>;  // best of at most 128 entries
 using RegCacheGV = RegCacheT<1, true>;   // the same with the visited ids in global memory (user queries)
 using RegCache2GV = RegCacheT<2, true>;
+using RegCacheAny = RegCacheT<1, false, true>;  // LDS table of any multiple of 64 slots (user queries)
+using RegCache2Any = RegCacheT<2, false, true>;
 
 }  // namespace ggnn

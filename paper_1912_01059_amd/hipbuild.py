@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libggnn.so")
-SOURCES = ["ggnn_search_reg.hip", "ggnn_search_split.hip", "ggnn_search_gv.hip", "ggnn_search_lds.hip", "ggnn_build.hip", "ggnn_api.hip"]
+SOURCES = ["ggnn_search_reg.hip", "ggnn_search_split.hip", "ggnn_search_gv.hip", "ggnn_search_any.hip", "ggnn_search_lds.hip", "ggnn_build.hip", "ggnn_api.hip"]
 # -ffp-contract=off: float32 arithmetic is exactly what the source says (fused multiply-adds are
 # written out where they are wanted), which the bit-for-bit reproducible distances rely on.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
