@@ -78,7 +78,7 @@ def test_query_small_capacities_and_iteration_limit(ggnn, R, sift10k, sift10k_or
     og = sift10k_oracle_graph
     g = to_gpu_graph(ggnn, og, dev(base))
     q = dev(queries[:300])
-    for P, V, it in [(4, 16, 16), (8, 64, 10), (100, 500, 500), (64, 384, 1), (64, 5000, 5000), (100, 9000, 9000)]:
+    for P, V, it in [(4, 16, 16), (8, 64, 10), (100, 500, 500), (64, 384, 1), (64, 5000, 5000), (100, 9000, 9000), (64, 385, 385), (32, 777, 700)]:
         ids, d, cnt = g.query(q, 10, 10, 0.4, pq_cap=P, visited_cap=V, max_iter=it, every_layer=True, counters=True)
         rids, rd, rcnt = og.query(queries[:300], 10, 10, 0.4, pq_cap=P, visited_cap=V, max_iter=it, every_layer=True,
                                   counters=True)
