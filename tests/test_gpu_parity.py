@@ -463,3 +463,34 @@ def test_global_visited_table_matches_lds_table_and_oracle(ggnn, R, sift10k, sif
     rids, rd, rcnt = og3.query(q3, 10, 10, 0.6, visited_cap=600, every_layer=True, counters=True)
     assert_same_results(ids, d, rids, rd)
     check_counters(c, rcnt)
+
+
+# ------------------------------------------------------------------------------ capture into a HIP graph
+
+def test_query_replayed_from_a_hip_graph(ggnn, R, sift10k, sift10k_oracle_graph):
+    """A batch below the two-launch threshold is one kernel launch and no allocation, so it can be
+    captured into a HIP graph: every replay, with eager work and synchronisations in between and new
+    queries in the captured input buffer, gives the oracle's answers."""
+    base, queries, cfg = sift10k
+    og = sift10k_oracle_graph
+    g = to_gpu_graph(ggnn, og, dev(base))
+    Q, k = 256, 10
+    qbuf = dev(queries[:Q].copy())
+    ids = torch.empty((Q, k), dtype=torch.int32, device="cuda")
+    d = torch.empty((Q, k), dtype=torch.float32, device="cuda")
+    g.query(qbuf, k, 10, 0.3, every_layer=True, out=(ids, d))  # warm-up outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        g.query(qbuf, k, 10, 0.3, every_layer=True, out=(ids, d), asynchronous=True)
+    for rep in range(4):
+        part = queries[rep * 150: rep * 150 + Q].copy()
+        qbuf.copy_(dev(part))
+        ids.fill_(-7)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        rids, rd = og.query(part, k, 10, 0.3, every_layer=True)
+        assert_same_results(ids, d, rids, rd)
+        eager_ids, eager_d = g.query(qbuf, k, 10, 0.3, every_layer=True)  # eager work between the replays
+        assert torch.equal(eager_ids, ids)
