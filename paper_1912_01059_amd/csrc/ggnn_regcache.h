@@ -465,7 +465,9 @@ struct RegCacheT {
     }
     wave_sync();
     GGNN_TICK(4);  // compaction
-    constexpr int RPP = RowSched<DT, PASSES>::rows_per_pass, NP = RowSched<DT, PASSES>::passes;
+    // rows of one chunk per lane (128 bytes) cost four registers each: a third pass is in flight
+    constexpr int RPP = RowSched<DT, PASSES>::rows_per_pass;
+    constexpr int NP = (Elem<DT>::lanes == kRowLanes && NCH == 1) ? RowSched<DT, PASSES>::passes + 1 : RowSched<DT, PASSES>::passes;
     for (int b0 = 0; b0 < ns; b0 += RPP * NP) gather_sum<DT, NCH, METRIC, NP>(G, q, surv_row, surv_d, b0, ns);
     wave_sync();
     GGNN_TICK(5);  // gather + distances
