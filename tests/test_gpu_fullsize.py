@@ -154,3 +154,44 @@ def test_real_valued_workloads_at_full_size_sampled_parity(name, every):
     assert np.array_equal(cnt[sample][:, :2].astype(np.uint32), rcnt)
     gt, _ = R.bruteforce(base, queries[sample[:32]], k, metric=R.COSINE if cosine else R.L2)
     assert R.recall(ids[sample[:32]], gt) >= (0.5 if cosine else 0.9)
+
+
+def test_uint8_workload_subset_sampled_parity():
+    """A 4M-point subset of the 100M x 128 uint8 workload (generated on the GPU as the full set would be),
+    four levels: integer distances from byte dot products, 24 rows in flight.  Sampled queries must equal
+    the oracle's search of the same graph bit for bit; reported distances are the exact ones."""
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import ggnn_inputs
+    import paper_1912_01059_amd as ggnn
+    from oracle import ggnn_ref as R
+    ggnn.set_cache_mode(0)
+    cfg = ggnn_inputs.CONFIGS["sift100m_u8"]
+    dev = torch.device("cuda:0")
+    N = 4_000_000
+    b = ggnn_inputs.gmm_int_torch(N, 128, cfg["components"], cfg["sigma"], cfg["data_seed"], cfg["data_seed"] + 1, dev, "u8")
+    q = ggnn_inputs.gmm_int_torch(2000, 128, cfg["components"], cfg["sigma"], cfg["data_seed"], cfg["query_seed"], dev, "u8")
+    g = ggnn.build(b, 24, 4, seed=42, visited_cap=192, max_iter=192)
+    k = 10
+    ids, dists, cnt = g.query(q, k, 10, 0.08, visited_cap=128, every_layer=True, counters=True)
+    ids, dists, cnt = ids.cpu().numpy(), dists.cpu().numpy(), cnt.cpu().numpy()
+    base, queries = b.cpu().numpy(), q.cpu().numpy()
+    assert (ids >= 0).all() and (ids < N).all()
+    key = (dists.view(np.uint32).astype(np.uint64) << np.uint64(32)) | ids.astype(np.uint64)
+    assert (key[:, 1:] > key[:, :-1]).all()
+    sample = np.arange(0, len(queries), 20)
+    d2 = ((base[ids[sample]].astype(np.int64) - queries[sample][:, None, :].astype(np.int64)) ** 2).sum(2)
+    assert np.array_equal(dists[sample], np.sqrt(d2.astype(np.float32)))
+    og = R.Graph(base, 24, 4, seed=42)
+    for l in range(g.L):
+        e, tl, tb = g.export_layer(l)
+        og.edges(l)[:] = e
+        if l >= 1:
+            og.to_lower(l)[:] = tl
+            og.to_base(l)[:] = tb
+    _, mean, mx = g.export_dnn()
+    og.stats()[:] = (mean, mx)
+    rids, rd, rcnt = og.query(queries[sample], k, 10, 0.08, visited_cap=128, every_layer=True, counters=True)
+    assert np.array_equal(ids[sample], rids)
+    assert np.array_equal(dists[sample].view(np.uint32), rd.view(np.uint32))
+    assert np.array_equal(cnt[sample][:, :2].astype(np.uint32), rcnt)
