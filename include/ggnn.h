@@ -37,6 +37,7 @@ extern "C" {
 #endif
 
 #define GGNN_MAX_LEVELS 8
+#define GGNN_STATIC_SCRATCH_BYTES (128u << 20) /* workspace of ggnn_query_static, per GPU */
 #define GGNN_ROW_LANES 8
 #define GGNN_WIDE_ROW_LANES 64
 
@@ -148,6 +149,26 @@ int ggnn_query(const ggnn_graph* g, const void* queries_dev, int64_t Q, int32_t 
 int ggnn_query_ex(const ggnn_graph* g, const void* queries_dev, int64_t Q, int32_t k, int32_t beam, float slack,
                   int32_t pq_cap, int32_t visited_cap, int32_t max_iter, int32_t every_layer, void* stream,
                   int32_t* ids_dev, float* dists_dev, uint32_t* counters_dev, int32_t asynchronous);
+
+/* For callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  The every-layer search of ggnn_query_ex in its two-launch form
+ * (upper layers; counting sort of the queries by the layer-1 point reached; bottom layer, one
+ * contiguous part of the sorted order per XCD), with the workspace that ggnn_query_ex takes from the
+ * stream's memory pool replaced by a static array of GGNN_STATIC_SCRATCH_BYTES that is part of the
+ * library's code object (one copy per GPU, held until the process ends).  The call allocates and frees
+ * nothing, issues kernels only (no memset, no copy) and gives the results and counters of
+ * ggnn_query_ex(..., every_layer = 1, ...) bit for bit.
+ * Limits (GGNN_ERR_LIMIT / GGNN_ERR_INVALID otherwise): the graph has at least three levels; prioq
+ * <= 64 and max(beam, k) <= 128 (lists in registers); the workspace Q * (W * 512 + 40) + 512 + 4 *
+ * (min(n[1], 65536) + 1) bytes, W = 2 for max(beam, k) <= 64 and 3 beyond, fits the array: about 126 000
+ * queries for W = 2 and 84 000 for W = 3.
+ * Every call on a GPU uses that GPU's one array, which keeps the last call's contents (nothing in it
+ * needs clearing between calls: each call writes what it reads).  Calls that overlap in time on one GPU,
+ * from any stream or thread, race on it: serialise them.  The device that holds the graph must be current.
+ * Arguments as ggnn_query_ex; stream NULL = the graph's stream. */
+int ggnn_query_static(const ggnn_graph* g, const void* queries_dev, int64_t Q, int32_t k, int32_t beam, float slack,
+                      int32_t pq_cap, int32_t visited_cap, int32_t max_iter, void* stream, int32_t* ids_dev,
+                      float* dists_dev, uint32_t* counters_dev, int32_t asynchronous);
 
 /* Alg. 1 on the bottom layer alone, from start points the caller names instead of the top layer:
  * the search of a flat graph (import its rows as layer 0; the upper layers are not touched), or the

@@ -44,7 +44,7 @@ class BuildTimes(C.Structure):
 
 EXPORTS = [
     "ggnn_build", "ggnn_build_ex", "ggnn_graph_create", "ggnn_select", "ggnn_merge", "ggnn_sym",
-    "ggnn_build_steps", "ggnn_build_get_times", "ggnn_query", "ggnn_query_ex", "ggnn_query_from", "ggnn_graph_info",
+    "ggnn_build_steps", "ggnn_build_get_times", "ggnn_query", "ggnn_query_ex", "ggnn_query_static", "ggnn_query_from", "ggnn_graph_info",
     "ggnn_graph_export", "ggnn_graph_import", "ggnn_graph_export_dnn", "ggnn_graph_import_dnn",
     "ggnn_graph_export_inv_count", "ggnn_set_cache_mode", "ggnn_set_split_threshold", "ggnn_set_global_visited_threshold", "ggnn_gather_probe", "ggnn_merge_shards", "ggnn_free", "ggnn_last_error",
 ]
@@ -69,6 +69,7 @@ def lib():
         L.ggnn_build_get_times.argtypes = [vp, C.POINTER(BuildTimes)]
         L.ggnn_query.argtypes = [vp, vp, i64, i32, i32, f32, vp, vp]
         L.ggnn_query_ex.argtypes = [vp, vp, i64, i32, i32, f32, i32, i32, i32, i32, vp, vp, vp, vp, i32]
+        L.ggnn_query_static.argtypes = [vp, vp, i64, i32, i32, f32, i32, i32, i32, vp, vp, vp, vp, i32]
         L.ggnn_query_from.argtypes = [vp, vp, i64, i32, i32, f32, i32, i32, i32, vp, i32, vp, vp, vp, vp, i32]
         L.ggnn_graph_info.argtypes = [vp, C.POINTER(GraphDesc)]
         L.ggnn_graph_export.argtypes = [vp, i32, vp, vp, vp]
@@ -284,6 +285,20 @@ class Graph:
               counters=False, out=None, stream=None, asynchronous=False, start_ids=None):
         return query(self, queries, k, beam, slack, pq_cap, visited_cap, max_iter, every_layer, counters, out,
                      stream, asynchronous, start_ids)
+
+
+def query_static(graph, queries, k, beam, slack, out, pq_cap=0, visited_cap=0, max_iter=0, counters=None,
+                 stream=None, asynchronous=False):
+    """ggnn_query_static: the every-layer search with the library's static workspace.  Nothing is allocated
+    here either: `out` = (ids, dists) and, optionally, `counters` (Q x 4 int32) are the caller's tensors."""
+    import torch
+    ids, dists = out
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream
+    _check(lib().ggnn_query_static(graph.h, _dev_ptr(queries), queries.shape[0], k, beam, slack, pq_cap, visited_cap,
+                                   max_iter, C.c_void_p(stream), _dev_ptr(ids), _dev_ptr(dists),
+                                   _dev_ptr(counters) if counters is not None else None, 1 if asynchronous else 0))
+    return ids, dists
 
 
 def graph_create(base, K, levels, seed=42, metric=L2, segment_size=0, tau_build=0.0, refinements=2, pq_cap=0,

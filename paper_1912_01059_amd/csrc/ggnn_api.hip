@@ -5,6 +5,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -16,6 +17,12 @@ using namespace ggnn;
 
 static_assert(GGNN_ROW_LANES == kRowLanes && GGNN_WIDE_ROW_LANES == kWideRowLanes, "public constants and kernels disagree");
 static_assert(GGNN_MAX_LEVELS == kMaxLevels, "public constant and kernels disagree");
+
+// Workspace of ggnn_query_static (the two-launch path for callers that cannot allocate): one array per
+// GPU, part of the loaded code object, held until the process ends.  In host code this name only
+// stands for the symbol: the array's device address comes from hipGetSymbolAddress (scratch_ptr below).
+constexpr size_t kScratchBytes = (size_t)GGNN_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 
 namespace {
 
@@ -34,6 +41,25 @@ int fail(int code, const char* fmt, ...) {
     hipError_t e_ = (expr);                                                                        \
     if (e_ != hipSuccess) return fail(GGNN_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_));       \
   } while (0)
+
+// device address of `scratch` on the current device, looked up once per device
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+unsigned char* g_scratch_ptr[kMaxDevices] = {nullptr};
+int scratch_ptr(unsigned char** out) {
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(GGNN_ERR_LIMIT, "device %d: this build keeps a workspace for devices 0..%d", dev, kMaxDevices - 1);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return fail(GGNN_ERR_HIP, "hipGetSymbolAddress returned a null address for the workspace");
+    g_scratch_ptr[dev] = (unsigned char*)p;
+  }
+  *out = g_scratch_ptr[dev];
+  return GGNN_OK;
+}
 
 constexpr size_t kMaxLds = 160 * 1024;  // LDS of a compute unit on gfx950, all of which one workgroup may take
 int g_cache_mode = 0;  // 0: registers whenever best and prioq fit 64 entries, 1: always LDS
@@ -179,10 +205,52 @@ constexpr int32_t kVisGlobalMinIter = 1100;  // iteration limit from which user 
 int32_t g_vis_global_min_iter = kVisGlobalMinIter;
 bool g_vis_global_forced = false;  // set through ggnn_set_global_visited_threshold: applies whatever the batch size
 
+// Workspace of the two-launch path: the lists put aside after the upper layers (state), counters
+// (meta), the sort keys, the sorted order and the bins of the counting sort.
+struct SplitLayout {
+  size_t state_bytes, meta_bytes, q_bytes, total;
+  int32_t state_keys, shift, nbins;
+};
+SplitLayout split_layout(const GraphDev& G, int slots, int64_t Q) {
+  SplitLayout lay = {};
+  while (((G.n[1] - 1) >> lay.shift) >= kSortBins) lay.shift++;
+  lay.nbins = (int32_t)(((G.n[1] - 1) >> lay.shift) + 1);
+  lay.state_keys = (slots + 1) * kWave;
+  lay.state_bytes = (size_t)Q * lay.state_keys * sizeof(u64);
+  lay.meta_bytes = (size_t)Q * 8 * sizeof(int32_t);
+  lay.q_bytes = (((size_t)Q * sizeof(int32_t)) + 255) / 256 * 256;
+  lay.total = lay.state_bytes + lay.meta_bytes + 2 * lay.q_bytes + ((size_t)lay.nbins + 1) * sizeof(int32_t);
+  return lay;
+}
+// upper layers, counting sort of the queries by the layer-1 point reached, bottom layer; every word of
+// the workspace that is read has been written by an earlier step of the same call (the bins are cleared
+// by a fill kernel), so the workspace may hold anything on entry
+hipError_t launch_query_two(const GraphDev& G, int dtype, int metric, const void* queries, int64_t Q, int k,
+                            const SearchParams& sp, int slots, int32_t* ids, float* dists, uint32_t* counters,
+                            unsigned char* ws, const SplitLayout& lay, hipStream_t stream) {
+  SplitBufs sb = {};
+  sb.Q = Q;
+  sb.state_keys = lay.state_keys;
+  sb.state = (u64*)ws;
+  sb.meta = (int32_t*)(ws + lay.state_bytes);
+  sb.key = (int32_t*)(ws + lay.state_bytes + lay.meta_bytes);
+  int32_t* order = (int32_t*)(ws + lay.state_bytes + lay.meta_bytes + lay.q_bytes);
+  int32_t* bins = (int32_t*)(ws + lay.state_bytes + lay.meta_bytes + 2 * lay.q_bytes);
+  sb.phase = 1;
+  hipError_t e = launch_query_split(slots, G, dtype, metric, queries, Q, k, sp, ids, dists, counters, sb, stream);
+  if (e == hipSuccess) e = launch_sort_by_key(sb.key, Q, lay.shift, lay.nbins, bins, order, stream);
+  if (e == hipSuccess) {
+    sb.phase = 2;
+    sb.order = order;
+    sb.per = (int32_t)((Q + kXcds - 1) / kXcds);
+    e = launch_query_split(slots, G, dtype, metric, queries, Q, k, sp, ids, dists, counters, sb, stream);
+  }
+  return e;
+}
+
 hipError_t launch_query(const GraphDev& G, int dtype, int metric, const void* queries, int64_t Q, int k,
                         const SearchParams& sp, int every_layer, int32_t* ids, float* dists, uint32_t* counters,
                         hipStream_t stream) {
-  SplitBufs sb = {};
   const int slots = register_slots(sp, true);
   // wavefronts the GPU holds at once when the visited table is in LDS (256 compute units, at most 24
   // wavefronts each): a batch that fits gains nothing from a table in global memory, which is slower to probe
@@ -204,35 +272,14 @@ hipError_t launch_query(const GraphDev& G, int dtype, int metric, const void* qu
   }
   const bool split = every_layer && G.L >= 3 && !sp.start && slots >= 1 && Q >= g_split_min_queries;
   if (!split) return launch_query_whole(G, dtype, metric, queries, Q, k, sp, every_layer, ids, dists, counters, stream);
-  // workspace from the stream's memory pool: lists, counters, keys, order, bins
-  int shift = 0;
-  while (((G.n[1] - 1) >> shift) >= kSortBins) shift++;
-  const int nbins = (int)(((G.n[1] - 1) >> shift) + 1);
-  sb.Q = Q;
-  sb.state_keys = (slots + 1) * kWave;
-  const size_t state_bytes = (size_t)Q * sb.state_keys * sizeof(u64);
-  const size_t meta_bytes = (size_t)Q * 8 * sizeof(int32_t);
-  const size_t q_bytes = (((size_t)Q * sizeof(int32_t)) + 255) / 256 * 256;
-  const size_t total = state_bytes + meta_bytes + 2 * q_bytes + ((size_t)nbins + 1) * sizeof(int32_t);
+  // workspace from the stream's memory pool
+  const SplitLayout lay = split_layout(G, slots, Q);
   unsigned char* ws = nullptr;
-  if (hipMallocAsync((void**)&ws, total, stream) != hipSuccess) {
+  if (hipMallocAsync((void**)&ws, lay.total, stream) != hipSuccess) {
     (void)hipGetLastError();  // no workspace: the one-launch path needs none
     return launch_query_whole(G, dtype, metric, queries, Q, k, sp, every_layer, ids, dists, counters, stream);
   }
-  sb.state = (u64*)ws;
-  sb.meta = (int32_t*)(ws + state_bytes);
-  sb.key = (int32_t*)(ws + state_bytes + meta_bytes);
-  int32_t* order = (int32_t*)(ws + state_bytes + meta_bytes + q_bytes);
-  int32_t* bins = (int32_t*)(ws + state_bytes + meta_bytes + 2 * q_bytes);
-  sb.phase = 1;
-  hipError_t e = launch_query_split(slots, G, dtype, metric, queries, Q, k, sp, ids, dists, counters, sb, stream);
-  if (e == hipSuccess) e = launch_sort_by_key(sb.key, Q, shift, nbins, bins, order, stream);
-  if (e == hipSuccess) {
-    sb.phase = 2;
-    sb.order = order;
-    sb.per = (int32_t)((Q + kXcds - 1) / kXcds);
-    e = launch_query_split(slots, G, dtype, metric, queries, Q, k, sp, ids, dists, counters, sb, stream);
-  }
+  const hipError_t e = launch_query_two(G, dtype, metric, queries, Q, k, sp, slots, ids, dists, counters, ws, lay, stream);
   const hipError_t f = hipFreeAsync(ws, stream);
   return e != hipSuccess ? e : f;
 }
@@ -633,6 +680,43 @@ int ggnn_query_from(const ggnn_graph* g, const void* queries_dev, int64_t Q, int
 int ggnn_query(const ggnn_graph* g, const void* queries_dev, int64_t Q, int32_t k, int32_t beam, float slack,
                int32_t* ids_dev, float* dists_dev) {
   return ggnn_query_ex(g, queries_dev, Q, k, beam, slack, 0, 0, 0, 0, nullptr, ids_dev, dists_dev, nullptr, 0);
+}
+
+int ggnn_query_static(const ggnn_graph* g, const void* queries_dev, int64_t Q, int32_t k, int32_t beam, float slack,
+                      int32_t pq_cap, int32_t visited_cap, int32_t max_iter, void* stream, int32_t* ids_dev,
+                      float* dists_dev, uint32_t* counters_dev, int32_t asynchronous) {
+  if (!g) return fail(GGNN_ERR_INVALID, "graph is NULL");
+  if (Q < 0 || Q > 0x7FFFFFFFll) return fail(GGNN_ERR_INVALID, "Q = %lld outside [0, 2^31)", (long long)Q);
+  if (Q == 0) return GGNN_OK;
+  if (!queries_dev || !ids_dev || !dists_dev) return fail(GGNN_ERR_INVALID, "NULL device pointer");
+  if (((uintptr_t)queries_dev) % 16 != 0) return fail(GGNN_ERR_INVALID, "queries_dev is not 16-byte aligned");
+  if (k < 1) return fail(GGNN_ERR_INVALID, "k = %d must be positive", k);
+  if (beam < 0 || !(slack >= 0.0f)) return fail(GGNN_ERR_INVALID, "beam and slack must not be negative");
+  if (g->L < 3) return fail(GGNN_ERR_INVALID, "the two-launch search needs at least three levels, the graph has %d", g->L);
+  const int B = beam > k ? beam : k;
+  const int P = pq_cap > 0 ? pq_cap : 64;
+  const int V = visited_cap > 0 ? visited_cap : (B >= 100 ? 896 : 384);
+  const int it = max_iter > 0 ? max_iter : V;
+  if (P > kWave || B > 2 * kWave)
+    return fail(GGNN_ERR_LIMIT, "the two-launch search keeps its lists in registers: prioq <= 64 and best <= 128 (got %d, %d)", P, B);
+  SearchParams sp;
+  int rc = make_search_params(B, P, V, it, slack, g->stats[1], &sp, true);
+  if (rc != GGNN_OK) return rc;
+  const int slots = B <= kWave ? 1 : 2;
+  const size_t need_lds = slots == 1 ? RegCache::lds_bytes(sp) : RegCache2::lds_bytes(sp);
+  if (need_lds > kMaxLds) return fail(GGNN_ERR_LIMIT, "an iteration limit of %d needs %zu bytes of LDS, limit %zu", it, need_lds, kMaxLds);
+  GraphDev G = device_view(g);
+  const SplitLayout lay = split_layout(G, slots, Q);
+  if (lay.total > kScratchBytes)
+    return fail(GGNN_ERR_LIMIT, "%lld queries need a workspace of %zu bytes; the static workspace holds %zu (about %lld queries)",
+                (long long)Q, lay.total, kScratchBytes, (long long)(kScratchBytes / (lay.total / (size_t)Q + 1)));
+  unsigned char* ws = nullptr;
+  rc = scratch_ptr(&ws);
+  if (rc != GGNN_OK) return rc;
+  hipStream_t st = stream ? (hipStream_t)stream : g->stream;
+  HIP_TRY(launch_query_two(G, row_dtype(g), g->metric, queries_dev, Q, k, sp, slots, ids_dev, dists_dev, counters_dev, ws, lay, st));
+  if (!asynchronous) HIP_TRY(hipStreamSynchronize(st));
+  return GGNN_OK;
 }
 
 int ggnn_graph_info(const ggnn_graph* g, ggnn_graph_desc* out) {
