@@ -146,6 +146,24 @@ def test_distance_summation_tree_is_the_documented_one(D, lanes):
     assert hits > 0  # the inputs really do distinguish summation orders
 
 
+@pytest.mark.parametrize("D", [64, 128, 256])
+def test_both_summation_trees_stay_within_the_float64_bound(D):
+    """The number of accumulators of the summation tree (8, or 64 for long rows) is a convention shared
+    with the GPU kernels, not something the paper fixes: whatever the width, the result must stay within
+    the rounding bound of the float64 distance, and on integer-valued rows (exact sums) the two widths
+    must give the same bits."""
+    rng = np.random.default_rng(100 + D)
+    for _ in range(40):
+        q = rng.standard_normal(D).astype(np.float32)
+        x = rng.standard_normal(D).astype(np.float32)
+        ref = np.sqrt(((q.astype(np.float64) - x.astype(np.float64)) ** 2).sum())
+        for lanes in (8, 64):
+            assert abs(R.distance(q, x, lanes=lanes) - ref) <= (D + 4) * 2.0 ** -24 * ref
+        qi = rng.integers(0, 256, D).astype(np.float32)
+        xi = rng.integers(0, 256, D).astype(np.float32)
+        assert R.distance(qi, xi, lanes=8) == R.distance(qi, xi, lanes=64)
+
+
 def _fma32(a, b, c):
     # float32 fma through exact rational arithmetic
     from fractions import Fraction
