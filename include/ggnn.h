@@ -11,8 +11,8 @@
  *  - Pointers named *_dev are device (HBM) pointers owned by the caller; pointers named
  *    *_host are host pointers owned by the caller.  The library never frees them.
  *  - Vectors are row-major, D elements per row, rows 16-byte aligned (D*sizeof(element)
- *    must be a multiple of 16).  Ids are int32; offsets into the graph's own arrays are 64-bit,
- *    byte offsets into the vector array 32-bit (hence the size limit below).
+ *    must be a multiple of 16).  Ids are int32 (N < 2^31); offsets into the graph's own arrays and into
+ *    the vector array are 64-bit (arrays below 4 GiB are served by kernels that use 32-bit byte offsets).
  *  - `base_dev` is BORROWED by the graph and must outlive it (it is not copied, except
  *    that a cosine graph owns a unit-length float32 copy).
  *  - All work is issued on the stream given at creation (or per call for queries); calls
@@ -24,9 +24,8 @@
  *    acc = fma(t, t, acc) over its chunks in ascending order, and the R lanes are combined
  *    by a butterfly (distance R/2, ..., 2, 1).  R = GGNN_ROW_LANES for rows of at most 1024
  *    bytes (for cosine: of the float32 unit-length copy), GGNN_WIDE_ROW_LANES for longer rows.
- *  - Row lengths: a multiple of 16 bytes; float32 D <= 1024, uint8 D <= 256.  The vector array (for
- *    cosine: its float32 unit-length copy) must be smaller than 4 GiB: rows are addressed with 32-bit
- *    byte offsets (GGNN_ERR_LIMIT otherwise).
+ *  - Row lengths: a multiple of 16 bytes; float32 D <= 1024, uint8 D <= 256.  The vector array may have
+ *    any size the GPU holds (the 12.8 GB of 10^8 x 128 uint8 rows included).
  */
 #ifndef GGNN_H
 #define GGNN_H
@@ -51,7 +50,7 @@ typedef enum {
   GGNN_ERR_INVALID = -1, /* bad argument (null pointer, size out of range, ...) */
   GGNN_ERR_MEMORY = -2,  /* device or host allocation failed                    */
   GGNN_ERR_HIP = -3,     /* a HIP runtime call or kernel launch failed          */
-  GGNN_ERR_LIMIT = -4    /* a capacity exceeds what one workgroup's LDS holds, or the vector array is too large */
+  GGNN_ERR_LIMIT = -4    /* a capacity exceeds what one workgroup's LDS (or the static workspace) holds */
 } ggnn_status;
 
 /* Construction parameters (appendix "Choosing Search-Graph Construction Parameters").

@@ -10,6 +10,7 @@
 #include <vector>
 
 #include "ggnn.h"
+#include "ggnn_geometry.h"
 #include "ggnn_launch.h"
 #include "ggnn_regcache.h"
 
@@ -64,43 +65,6 @@ int scratch_ptr(unsigned char** out) {
 constexpr size_t kMaxLds = 160 * 1024;  // LDS of a compute unit on gfx950, all of which one workgroup may take
 int g_cache_mode = 0;  // 0: registers whenever best and prioq fit 64 entries, 1: always LDS
 
-uint64_t mix64_host(uint64_t x) {
-  x ^= x >> 30; x *= 0xBF58476D1CE4E5B9ull;
-  x ^= x >> 27; x *= 0x94D049BB133111EBull;
-  x ^= x >> 31;
-  return x;
-}
-
-int64_t ipow(int64_t b, int e) {
-  int64_t r = 1;
-  for (int i = 0; i < e; i++) r *= b;
-  return r;
-}
-
-// Sec. 4.3 / appendix "Graph Size": growth factor and layer sizes
-int geometry(int64_t N, int s, int L, int* g_out, int64_t* n, int64_t* G) {
-  const double root = pow((double)N / (double)s, 1.0 / (double)(L - 1));
-  int64_t cand[2] = {(int64_t)floor(root), (int64_t)ceil(root)};
-  int64_t g = -1;
-  double err = 0.0;
-  for (int i = 0; i < 2; i++) {
-    int64_t c = cand[i] < 1 ? 1 : cand[i];
-    double e = fabs((double)N / (double)ipow(c, L - 1) - (double)s);
-    if (g < 0 || e < err) { g = c; err = e; }
-  }
-  for (int l = 0; l < L; l++) {
-    G[l] = ipow(g, L - 1 - l);
-    n[l] = (l == 0) ? N : (int64_t)s * G[l];
-  }
-  if (G[0] > N) return -1;
-  const int64_t s0_min = N / G[0];
-  const int64_t share_max = ((int64_t)s + g - 1) / g;
-  if (s0_min < share_max || s0_min < 2) return -1;
-  if (L > 2 && n[1] > N) return -1;
-  *g_out = (int)g;
-  return 0;
-}
-
 int next_pow2(int v) {
   int p = 1;
   while (p < v) p <<= 1;
@@ -146,6 +110,7 @@ GraphDev device_view(const ggnn_graph* g) {
   const int esize = (g->norm || g->dtype == GGNN_F32) ? 4 : 1;
   G.row_bytes = g->D * esize;
   G.nchunks = G.row_bytes / 16;
+  G.addr32 = ((uint64_t)g->N * (uint64_t)G.row_bytes < (1ull << 32)) ? 1 : 0;
   for (int l = 0; l < g->L; l++) {
     G.n[l] = g->n[l];
     G.edges[l] = g->edges[l];
@@ -153,11 +118,7 @@ GraphDev device_view(const ggnn_graph* g) {
     G.to_base[l] = g->to_base[l];
   }
   G.G0 = g->G[0];
-  int h = 1;
-  while ((((int64_t)1) << (2 * h)) < g->N) h++;
-  G.fbits = h;
-  for (int r = 0; r < 4; r++) G.fkey[r] = (uint32_t)mix64_host(g->seed + 0x9E3779B97F4A7C15ull * (uint64_t)(r + 1));
-  G.seed = g->seed;
+  partition_keys(g->N, g->seed, &G);
   return G;
 }
 int row_dtype(const ggnn_graph* g) { return g->norm ? GGNN_F32 : g->dtype; }
@@ -190,10 +151,11 @@ hipError_t launch_query_whole(const GraphDev& G, int dtype, int metric, const vo
                               hipStream_t stream) {
   const int slots = register_slots(sp, true);
   // beyond 384 iterations a power-of-two table would be larger than 1024 slots: size it to the limit
+  const bool wide = !G.addr32;  // arrays of 4 GiB and more: the variants with 64-bit row offsets
   if (slots >= 1 && 2 * sp.max_iter + 256 > 1024)
-    return launch_query_any(slots, G, dtype, metric, queries, Q, k, sp, every_layer, ids, dists, counters, stream);
-  if (slots == 1) return launch_query_reg(G, dtype, metric, queries, Q, k, sp, every_layer, ids, dists, counters, stream);
-  if (slots == 2) return launch_query_reg2(G, dtype, metric, queries, Q, k, sp, every_layer, ids, dists, counters, stream);
+    return (wide ? launch_query_any_wide : launch_query_any)(slots, G, dtype, metric, queries, Q, k, sp, every_layer, ids, dists, counters, stream);
+  if (slots == 1) return (wide ? launch_query_reg_wide : launch_query_reg)(G, dtype, metric, queries, Q, k, sp, every_layer, ids, dists, counters, stream);
+  if (slots == 2) return (wide ? launch_query_reg2_wide : launch_query_reg2)(G, dtype, metric, queries, Q, k, sp, every_layer, ids, dists, counters, stream);
   return launch_query_lds(G, dtype, metric, queries, Q, k, sp, every_layer, ids, dists, counters, stream);
 }
 
@@ -237,13 +199,14 @@ hipError_t launch_query_two(const GraphDev& G, int dtype, int metric, const void
   int32_t* order = (int32_t*)(ws + lay.state_bytes + lay.meta_bytes + lay.q_bytes);
   int32_t* bins = (int32_t*)(ws + lay.state_bytes + lay.meta_bytes + 2 * lay.q_bytes);
   sb.phase = 1;
-  hipError_t e = launch_query_split(slots, G, dtype, metric, queries, Q, k, sp, ids, dists, counters, sb, stream);
+  const auto launch_phase = G.addr32 ? launch_query_split : launch_query_split_wide;
+  hipError_t e = launch_phase(slots, G, dtype, metric, queries, Q, k, sp, ids, dists, counters, sb, stream);
   if (e == hipSuccess) e = launch_sort_by_key(sb.key, Q, lay.shift, lay.nbins, bins, order, stream);
   if (e == hipSuccess) {
     sb.phase = 2;
     sb.order = order;
     sb.per = (int32_t)((Q + kXcds - 1) / kXcds);
-    e = launch_query_split(slots, G, dtype, metric, queries, Q, k, sp, ids, dists, counters, sb, stream);
+    e = launch_phase(slots, G, dtype, metric, queries, Q, k, sp, ids, dists, counters, sb, stream);
   }
   return e;
 }
@@ -264,7 +227,7 @@ hipError_t launch_query(const GraphDev& G, int dtype, int metric, const void* qu
     if (hipMallocAsync((void**)&vis, bytes, stream) == hipSuccess) {
       SearchParams spv = sp;
       spv.vis = vis;
-      const hipError_t e = launch_query_gv(slots, G, dtype, metric, queries, Q, k, spv, every_layer, ids, dists, counters, stream);
+      const hipError_t e = (G.addr32 ? launch_query_gv : launch_query_gv_wide)(slots, G, dtype, metric, queries, Q, k, spv, every_layer, ids, dists, counters, stream);
       const hipError_t f = hipFreeAsync(vis, stream);
       return e != hipSuccess ? e : f;
     }
@@ -285,14 +248,14 @@ hipError_t launch_query(const GraphDev& G, int dtype, int metric, const void* qu
 }
 hipError_t launch_merge(const GraphDev& G, int dtype, int metric, int l_top, int l_m, const SearchParams& sp,
                         int32_t* out_rows, float* dnn1, unsigned long long* work, hipStream_t stream) {
-  return register_slots(sp, false) == 1 ? launch_merge_reg(G, dtype, metric, l_top, l_m, sp, out_rows, dnn1, work, stream)
-                           : launch_merge_lds(G, dtype, metric, l_top, l_m, sp, out_rows, dnn1, work, stream);
+  if (register_slots(sp, false) != 1) return launch_merge_lds(G, dtype, metric, l_top, l_m, sp, out_rows, dnn1, work, stream);
+  return (G.addr32 ? launch_merge_reg : launch_merge_reg_wide)(G, dtype, metric, l_top, l_m, sp, out_rows, dnn1, work, stream);
 }
 hipError_t launch_sym_search(const GraphDev& G, int dtype, int metric, int layer, int round, float w_mid,
                              const SearchParams& sp, const SymBuffers& sb, unsigned long long* work,
                              hipStream_t stream) {
-  return register_slots(sp, false) == 1 ? launch_sym_search_reg(G, dtype, metric, layer, round, w_mid, sp, sb, work, stream)
-                           : launch_sym_search_lds(G, dtype, metric, layer, round, w_mid, sp, sb, work, stream);
+  if (register_slots(sp, false) != 1) return launch_sym_search_lds(G, dtype, metric, layer, round, w_mid, sp, sb, work, stream);
+  return (G.addr32 ? launch_sym_search_reg : launch_sym_search_reg_wide)(G, dtype, metric, layer, round, w_mid, sp, sb, work, stream);
 }
 
 int ensure_sym_buffers(ggnn_graph* g) {
@@ -422,12 +385,6 @@ int ggnn_graph_create(const void* base_dev, int64_t N, int32_t D, int32_t K, int
   if ((dtype == GGNN_F32 && D > 1024) || (dtype == GGNN_U8 && D > 256))
     return fail(GGNN_ERR_INVALID, "D = %d too large (float32: <= 1024, uint8: <= 256)", D);
   if (((uintptr_t)base_dev) % 16 != 0) return fail(GGNN_ERR_INVALID, "base_dev is not 16-byte aligned");
-  // the search kernels address rows with 32-bit byte offsets (for cosine: rows of the float32 copy)
-  const uint64_t array_bytes = (uint64_t)N * (uint64_t)D * (uint64_t)(metric == GGNN_COSINE ? 4 : esize);
-  if (array_bytes >= (1ull << 32))
-    return fail(GGNN_ERR_LIMIT, "the vector array holds %llu bytes; this build accepts arrays below 4 GiB",
-                (unsigned long long)array_bytes);
-
   ggnn_graph* g = new (std::nothrow) ggnn_graph();
   if (!g) return fail(GGNN_ERR_MEMORY, "host allocation failed");
   g->N = N; g->D = D; g->K = K; g->L = levels; g->s = s; g->dtype = dtype; g->metric = metric; g->seed = seed;

@@ -65,9 +65,9 @@ hipError_t launch_sort_by_key(const int32_t* key, int64_t Q, int shift, int nbin
 // the fixed order of every distance; RL lanes per row (8, or 64 for rows longer than 1024 bytes)
 template <int RL>
 __global__ __launch_bounds__(kWave) void normalise_kernel(const uint8_t* __restrict__ base, int dtype, int64_t N,
-                                                          int D, float* __restrict__ out) {
+                                                          int D, float* __restrict__ out, int64_t first) {
   const int lane = threadIdx.x, sub = lane & (RL - 1), grp = lane / RL;
-  const int64_t row = (int64_t)blockIdx.x * (kWave / RL) + grp;
+  const int64_t row = (first + blockIdx.x) * (kWave / RL) + grp;
   const bool act = row < N;
   const int per = (dtype == 1) ? 16 : 4;
   const int nchunks = (D + per - 1) / per;
@@ -97,11 +97,12 @@ __global__ __launch_bounds__(kWave) void normalise_kernel(const uint8_t* __restr
 }
 hipError_t launch_normalise(const void* base, int dtype, int64_t N, int D, float* out, hipStream_t stream) {
   // the unit-length copy is float32: its row length decides how many lanes share a row
-  if ((size_t)D * 4 > (size_t)kRowLanes * 8 * 16) {
-    normalise_kernel<kWideRowLanes><<<(unsigned)N, kWave, 0, stream>>>((const uint8_t*)base, dtype, N, D, out);
-  } else {
-    const int64_t blocks = (N + kRowsPerPass - 1) / kRowsPerPass;
-    normalise_kernel<kRowLanes><<<(unsigned)blocks, kWave, 0, stream>>>((const uint8_t*)base, dtype, N, D, out);
+  const bool wide = (size_t)D * 4 > (size_t)kRowLanes * 8 * 16;
+  const int64_t blocks = wide ? N : (N + kRowsPerPass - 1) / kRowsPerPass;
+  for (int64_t first = 0; first < blocks; first += kMaxBlocksPerLaunch) {
+    const unsigned nb = chunk_blocks(blocks, first);
+    if (wide) normalise_kernel<kWideRowLanes><<<nb, kWave, 0, stream>>>((const uint8_t*)base, dtype, N, D, out, first);
+    else normalise_kernel<kRowLanes><<<nb, kWave, 0, stream>>>((const uint8_t*)base, dtype, N, D, out, first);
   }
   return hipGetLastError();
 }
@@ -114,12 +115,13 @@ __device__ inline double select_uniform(uint64_t seed, int l_top, int64_t row) {
   return ((double)(x >> 12) + 0.5) * (1.0 / 4503599627370496.0);
 }
 __global__ __launch_bounds__(kWave) void select_kernel(GraphDev G, int l_top, const float* __restrict__ dnn1,
-                                                       int32_t* __restrict__ to_lower, int32_t* __restrict__ to_base) {
+                                                       int32_t* __restrict__ to_lower, int32_t* __restrict__ to_base,
+                                                       int64_t first) {
   __shared__ double key[kWave];
   __shared__ int32_t mem[kWave];
   const int lane = threadIdx.x;
   const int lc = l_top - 1;
-  const int64_t child = blockIdx.x;
+  const int64_t child = first + blockIdx.x;
   const int64_t t = child / G.g;
   const int j = (int)(child % G.g);
   const int share = (int)(((int64_t)(j + 1) * G.s) / G.g - ((int64_t)j * G.s) / G.g);
@@ -157,7 +159,8 @@ __global__ __launch_bounds__(kWave) void select_kernel(GraphDev G, int l_top, co
 hipError_t launch_select(const GraphDev& G, int l_top, const float* dnn1, int32_t* to_lower, int32_t* to_base,
                          hipStream_t stream) {
   const int64_t children = G.n[l_top] / G.s * G.g;
-  select_kernel<<<(unsigned)children, kWave, 0, stream>>>(G, l_top, dnn1, to_lower, to_base);
+  for (int64_t first = 0; first < children; first += kMaxBlocksPerLaunch)
+    select_kernel<<<chunk_blocks(children, first), kWave, 0, stream>>>(G, l_top, dnn1, to_lower, to_base, first);
   return hipGetLastError();
 }
 
@@ -343,10 +346,12 @@ __global__ void sym_apply_kernel(GraphDev G, int layer, SymBuffers sb, int32_t* 
 // folds them into one word per wavefront, so that only the gather itself is timed.
 __global__ __launch_bounds__(kWave) void gather_probe_kernel(const uint8_t* __restrict__ rows, int row_bytes,
                                                              const int32_t* __restrict__ ids, int64_t n,
-                                                             int rows_per_wave, uint32_t* __restrict__ out) {
+                                                             int rows_per_wave, uint32_t* __restrict__ out,
+                                                             int64_t first_block) {
   const int lane = threadIdx.x, sub = lane & (kRowLanes - 1), grp = lane / kRowLanes;
   const int nchunks = row_bytes / 16;
-  const int64_t first = (int64_t)blockIdx.x * rows_per_wave;
+  const int64_t block = first_block + blockIdx.x;
+  const int64_t first = block * rows_per_wave;
   uint32_t acc = 0;
   for (int r0 = 0; r0 < rows_per_wave; r0 += 3 * kRowsPerPass) {
     uint4 v[3][4];
@@ -367,12 +372,14 @@ __global__ __launch_bounds__(kWave) void gather_probe_kernel(const uint8_t* __re
 #pragma unroll
       for (int ch = 0; ch < 4; ch++) acc ^= v[ps][ch].x ^ v[ps][ch].y ^ v[ps][ch].z ^ v[ps][ch].w;
   }
-  out[(size_t)blockIdx.x * kWave + lane] = acc;
+  out[(size_t)block * kWave + lane] = acc;
 }
 hipError_t launch_gather_probe(const void* rows, int row_bytes, const int32_t* ids, int64_t n, int rows_per_wave,
                                uint32_t* out, hipStream_t stream) {
   const int64_t waves = (n + rows_per_wave - 1) / rows_per_wave;
-  gather_probe_kernel<<<(unsigned)waves, kWave, 0, stream>>>((const uint8_t*)rows, row_bytes, ids, n, rows_per_wave, out);
+  for (int64_t first = 0; first < waves; first += kMaxBlocksPerLaunch)
+    gather_probe_kernel<<<chunk_blocks(waves, first), kWave, 0, stream>>>((const uint8_t*)rows, row_bytes, ids, n,
+                                                                         rows_per_wave, out, first);
   return hipGetLastError();
 }
 
@@ -383,11 +390,12 @@ hipError_t launch_gather_probe(const void* rows, int row_bytes, const int32_t* i
 __global__ __launch_bounds__(kWave) void merge_shards_kernel(int S, int64_t Q, int k, const int32_t* __restrict__ ids,
                                                              const float* __restrict__ dists,
                                                              const int32_t* __restrict__ offsets,
-                                                             int32_t* __restrict__ out_ids, float* __restrict__ out_dists) {
+                                                             int32_t* __restrict__ out_ids, float* __restrict__ out_dists,
+                                                             int64_t first) {
   extern __shared__ __align__(16) unsigned char lds[];
   u64* keys = (u64*)lds;
   const int lane = threadIdx.x;
-  const int64_t q = blockIdx.x;
+  const int64_t q = first + blockIdx.x;
   const int n = S * k;
   for (int i = lane; i < n; i += kWave) {
     const int s = i / k, j = i - s * k;
@@ -413,7 +421,9 @@ __global__ __launch_bounds__(kWave) void merge_shards_kernel(int S, int64_t Q, i
 hipError_t launch_merge_shards(int S, int64_t Q, int k, const int32_t* ids, const float* dists, const int32_t* offsets,
                                int32_t* out_ids, float* out_dists, hipStream_t stream) {
   if (Q <= 0) return hipSuccess;
-  merge_shards_kernel<<<(unsigned)Q, kWave, (size_t)S * k * 8, stream>>>(S, Q, k, ids, dists, offsets, out_ids, out_dists);
+  for (int64_t first = 0; first < Q; first += kMaxBlocksPerLaunch)
+    merge_shards_kernel<<<chunk_blocks(Q, first), kWave, (size_t)S * k * 8, stream>>>(S, Q, k, ids, dists, offsets, out_ids,
+                                                                                      out_dists, first);
   return hipGetLastError();
 }
 

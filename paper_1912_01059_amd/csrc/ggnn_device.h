@@ -21,6 +21,7 @@ struct GraphDev {
   int64_t N;
   int32_t D, K, L, s, g;
   int32_t row_bytes, nchunks;  // bytes per row, 16-byte chunks per row
+  int32_t addr32;              // 1: the vector array is smaller than 4 GiB (host side: which kernel variant to launch)
   int64_t n[kMaxLevels];
   const int32_t* edges[kMaxLevels];
   const int32_t* to_lower[kMaxLevels];
@@ -70,19 +71,21 @@ __device__ __forceinline__ void wave_sync() { __syncthreads(); }
 __device__ __forceinline__ int lane_id() { return threadIdx.x; }
 
 // ---- partition permutation (bottom-layer segments): 4-round Feistel network with cycle walking
-__device__ __forceinline__ uint32_t mix32(uint32_t h) {
+// (host-callable as well: tests/host_index_sweep.cpp walks every index expression of the bottom layer
+// at full size on the CPU, under the address and undefined-behaviour sanitizers)
+__host__ __device__ __forceinline__ uint32_t mix32(uint32_t h) {
   h ^= h >> 16; h *= 0x85EBCA6Bu;
   h ^= h >> 13; h *= 0xC2B2AE35u;
   h ^= h >> 16;
   return h;
 }
-__device__ __forceinline__ uint64_t mix64(uint64_t x) {
+__host__ __device__ __forceinline__ uint64_t mix64(uint64_t x) {
   x ^= x >> 30; x *= 0xBF58476D1CE4E5B9ull;
   x ^= x >> 27; x *= 0x94D049BB133111EBull;
   x ^= x >> 31;
   return x;
 }
-__device__ inline int64_t perm_fwd(const GraphDev& G, int64_t p) {
+__host__ __device__ inline int64_t perm_fwd(const GraphDev& G, int64_t p) {
   const uint32_t mask = (uint32_t)((1ull << G.fbits) - 1);
   uint64_t x = (uint64_t)p;
   do {
@@ -96,7 +99,7 @@ __device__ inline int64_t perm_fwd(const GraphDev& G, int64_t p) {
   } while ((int64_t)x >= G.N);
   return (int64_t)x;
 }
-__device__ inline int64_t perm_inv(const GraphDev& G, int64_t row) {
+__host__ __device__ inline int64_t perm_inv(const GraphDev& G, int64_t row) {
   const uint32_t mask = (uint32_t)((1ull << G.fbits) - 1);
   uint64_t x = (uint64_t)row;
   do {
@@ -110,8 +113,8 @@ __device__ inline int64_t perm_inv(const GraphDev& G, int64_t row) {
   } while ((int64_t)x >= G.N);
   return (int64_t)x;
 }
-__device__ __forceinline__ int64_t seg0_lo(const GraphDev& G, int64_t j) { return (j * G.N) / G.G0; }
-__device__ __forceinline__ int64_t seg0_of_row(const GraphDev& G, int64_t row) {
+__host__ __device__ __forceinline__ int64_t seg0_lo(const GraphDev& G, int64_t j) { return (j * G.N) / G.G0; }
+__host__ __device__ __forceinline__ int64_t seg0_of_row(const GraphDev& G, int64_t row) {
   return ((perm_inv(G, row) + 1) * G.G0 - 1) / G.N;
 }
 
@@ -441,10 +444,14 @@ __device__ __forceinline__ float row_distance(const QueryRegs<DT, NCH>& q, const
 // the whole wavefront per long row), every load issued before the first use, then leaves the sum of
 // every row in surv_sum.  A pass takes kWave / lanes rows.  Lanes without a row read row 0 (their sums
 // are never stored), so nothing is spent on clearing registers or masking loads; the arithmetic of a
-// pass without rows is skipped.  All byte offsets fit 32 bits (the library accepts no larger array): the
-// address is the uniform base plus a 32-bit lane offset plus a constant per chunk.  FULL: every lane
-// owns NCH chunks of the row (no ragged tail).
-template <int DT, int NCH, int METRIC, int NP, bool FULL>
+// pass without rows is skipped.  A32: every byte offset into the array fits 32 bits, and the address is
+// the uniform base plus a 32-bit lane offset plus a constant per chunk; otherwise (arrays of 4 GiB and
+// more, served by kernel variants of their own so that the common case keeps its register budget) the
+// lane offset is formed in 64 bits.  FULL: every lane owns NCH chunks of the row (no ragged tail).
+__host__ __device__ __forceinline__ uint64_t row_offset(uint32_t row, uint32_t row_bytes, uint32_t sub) {
+  return (uint64_t)row * row_bytes + (uint64_t)sub * 16u;
+}
+template <int DT, int NCH, int METRIC, int NP, bool FULL, bool A32>
 __device__ __forceinline__ void gather_sum_t(const GraphDev& G, const QueryRegs<DT, NCH>& q, const int32_t* surv_row,
                                              float* surv_sum, int b0, int ns) {
   constexpr int RL = Elem<DT>::lanes, RPP = kWave / RL;
@@ -454,7 +461,9 @@ __device__ __forceinline__ void gather_sum_t(const GraphDev& G, const QueryRegs<
   for (int ps = 0; ps < NP; ps++) {
     const int r = b0 + ps * RPP + grp;
     const uint32_t row = (r < ns) ? (uint32_t)surv_row[r] : 0u;
-    const uint8_t* ptr = G.rows + (row * (uint32_t)G.row_bytes + (uint32_t)sub * 16u);
+    const uint8_t* ptr;
+    if (A32) ptr = G.rows + (uint32_t)row_offset(row, (uint32_t)G.row_bytes, (uint32_t)sub);
+    else ptr = G.rows + row_offset(row, (uint32_t)G.row_bytes, (uint32_t)sub);
 #pragma unroll
     for (int ch = 0; ch < NCH; ch++) {
       if (FULL) {
@@ -474,12 +483,12 @@ __device__ __forceinline__ void gather_sum_t(const GraphDev& G, const QueryRegs<
     }
   }
 }
-template <int DT, int NCH, int METRIC, int NP>
+template <int DT, int NCH, int METRIC, int NP, bool A32>
 __device__ __forceinline__ void gather_sum(const GraphDev& G, const QueryRegs<DT, NCH>& q, const int32_t* surv_row,
                                            float* surv_sum, int b0, int ns) {
   const bool full = G.nchunks == NCH * Elem<DT>::lanes;
-  if (full) gather_sum_t<DT, NCH, METRIC, NP, true>(G, q, surv_row, surv_sum, b0, ns);
-  else gather_sum_t<DT, NCH, METRIC, NP, false>(G, q, surv_row, surv_sum, b0, ns);
+  if (full) gather_sum_t<DT, NCH, METRIC, NP, true, A32>(G, q, surv_row, surv_sum, b0, ns);
+  else gather_sum_t<DT, NCH, METRIC, NP, false, A32>(G, q, surv_row, surv_sum, b0, ns);
 }
 
 // Alg. 2 Fetch.  Lane j holds proposal p (or -1).  Known points are dropped against the

@@ -10,6 +10,18 @@ namespace ggnn {
 // the work counters of the construction searches are spread over this many cache lines
 constexpr int kWorkSlots = 1024;
 
+// A dispatch counts the work-items of each grid dimension in 32 bits, so one launch of 64-lane
+// workgroups holds fewer than 2^26 of them: a launch of 10^8 workgroups does not fit, and what the
+// hardware then runs is not what was asked for.  Kernels that take one workgroup per item (query,
+// point, segment) are launched in chunks of at most kMaxBlocksPerLaunch workgroups on the same stream;
+// each launch is told its first item and the kernel adds blockIdx.x to it.  (A multiple of 8, so the
+// workgroup -> XCD assignment continues across chunks.)
+constexpr int64_t kMaxBlocksPerLaunch = (int64_t)1 << 24;
+inline unsigned chunk_blocks(int64_t n_items, int64_t first) {
+  const int64_t left = n_items - first;
+  return (unsigned)(left < kMaxBlocksPerLaunch ? left : kMaxBlocksPerLaunch);
+}
+
 // state of one symmetric-linking pass over a layer (device buffers owned by the graph)
 struct SymBuffers {
   int32_t* inv;       // n x ksym inverse links granted so far
@@ -26,7 +38,9 @@ struct SymBuffers {
 };
 
 // search kernels: best / prioq in registers (ggnn_search_reg.hip, capacities <= 64) or in LDS
-// (ggnn_search_lds.hip); launch_* picks the register variant whenever the capacities allow it
+// (ggnn_search_lds.hip); the API picks the register variant whenever the capacities allow it.
+// Every register variant exists twice: plain for vector arrays below 4 GiB (32-bit row offsets) and
+// `_wide` for larger arrays (64-bit row offsets; the *_wide.hip translation units).
 #define GGNN_SEARCH_LAUNCHERS(SUFFIX)                                                                              \
   hipError_t launch_query##SUFFIX(const GraphDev& G, int dtype, int metric, const void* queries, int64_t Q, int k, \
                                   const SearchParams& sp, int every_layer, int32_t* ids, float* dists,             \
@@ -38,24 +52,30 @@ struct SymBuffers {
                                        const SearchParams& sp, const SymBuffers& sb, unsigned long long* work,  \
                                        hipStream_t stream);
 GGNN_SEARCH_LAUNCHERS(_reg)
-hipError_t launch_query_reg2(const GraphDev& G, int dtype, int metric, const void* queries, int64_t Q, int k,
-                             const SearchParams& sp, int every_layer, int32_t* ids, float* dists, uint32_t* counters,
-                             hipStream_t stream);
-// ggnn_search_split.hip: launch sb.phase (1 or 2) of a large batch; slots = registers per lane of best (1 or 2)
-hipError_t launch_query_split(int slots, const GraphDev& G, int dtype, int metric, const void* queries, int64_t Q, int k,
-                              const SearchParams& sp, int32_t* ids, float* dists, uint32_t* counters,
-                              const SplitBufs& sb, hipStream_t stream);
-// ggnn_search_gv.hip: user queries with the visited ids in global memory (sp.vis: Q tables of
-// RegCacheGV::vis_slots(sp.max_iter) words); slots as above
-hipError_t launch_query_gv(int slots, const GraphDev& G, int dtype, int metric, const void* queries, int64_t Q, int k,
-                           const SearchParams& sp, int every_layer, int32_t* ids, float* dists, uint32_t* counters,
-                           hipStream_t stream);
-// ggnn_search_any.hip: user queries with an LDS table of any multiple of 64 slots; slots as above
-hipError_t launch_query_any(int slots, const GraphDev& G, int dtype, int metric, const void* queries, int64_t Q, int k,
-                            const SearchParams& sp, int every_layer, int32_t* ids, float* dists, uint32_t* counters,
-                            hipStream_t stream);
+GGNN_SEARCH_LAUNCHERS(_reg_wide)
 GGNN_SEARCH_LAUNCHERS(_lds)
 #undef GGNN_SEARCH_LAUNCHERS
+// slots = registers per lane of best (1 or 2)
+#define GGNN_QUERY_LAUNCHERS(SUFFIX)                                                                               \
+  /* best of up to 128 entries */                                                                                  \
+  hipError_t launch_query_reg2##SUFFIX(const GraphDev& G, int dtype, int metric, const void* queries, int64_t Q,   \
+                                       int k, const SearchParams& sp, int every_layer, int32_t* ids, float* dists, \
+                                       uint32_t* counters, hipStream_t stream);                                    \
+  /* ggnn_search_split.hip: launch sb.phase (1 or 2) of a large batch */                                           \
+  hipError_t launch_query_split##SUFFIX(int slots, const GraphDev& G, int dtype, int metric, const void* queries,  \
+                                        int64_t Q, int k, const SearchParams& sp, int32_t* ids, float* dists,      \
+                                        uint32_t* counters, const SplitBufs& sb, hipStream_t stream);              \
+  /* ggnn_search_gv.hip: visited ids in global memory (sp.vis: Q tables of RegCacheGV::vis_slots words) */        \
+  hipError_t launch_query_gv##SUFFIX(int slots, const GraphDev& G, int dtype, int metric, const void* queries,     \
+                                     int64_t Q, int k, const SearchParams& sp, int every_layer, int32_t* ids,      \
+                                     float* dists, uint32_t* counters, hipStream_t stream);                        \
+  /* ggnn_search_any.hip: LDS table of any multiple of 64 slots */                                                 \
+  hipError_t launch_query_any##SUFFIX(int slots, const GraphDev& G, int dtype, int metric, const void* queries,    \
+                                      int64_t Q, int k, const SearchParams& sp, int every_layer, int32_t* ids,     \
+                                      float* dists, uint32_t* counters, hipStream_t stream);
+GGNN_QUERY_LAUNCHERS()
+GGNN_QUERY_LAUNCHERS(_wide)
+#undef GGNN_QUERY_LAUNCHERS
 
 // construction kernels (ggnn_build.hip)
 hipError_t launch_gather_probe(const void* rows, int row_bytes, const int32_t* ids, int64_t n, int rows_per_wave,

@@ -36,37 +36,16 @@ __device__ __forceinline__ u64 read_lane_u64(u64 v, int lane) {
   return ((u64)hi << 32) | lo;
 }
 
-#ifdef GGNN_PHASE_TIMING
-// Debug build only: cycles spent per phase of an iteration, summed over all wavefronts.
-__device__ unsigned long long g_phase_cycles[16];
-#define GGNN_T0() unsigned long long t_ph = __builtin_readcyclecounter()
-#define GGNN_TICK(i)                                             \
-  do {                                                           \
-    unsigned long long t_now = __builtin_readcyclecounter();     \
-    ph[i] += (uint32_t)(t_now - t_ph);                           \
-    t_ph = t_now;                                                \
-  } while (0)
-#else
-#define GGNN_T0()
-#define GGNN_TICK(i)
-#endif
-
 // GV: the visited ids live in a table in global memory (one per query, handed in through
 // SearchParams::vis) instead of LDS, which then holds the rejected ids only: for searches of a thousand
 // iterations and more the LDS table is what limits the wavefronts a compute unit holds.
 // ANY: the LDS table may have any multiple of 64 slots (searches of a few hundred to a thousand
 // iterations, where the step to the next power of two would cost a wavefront per SIMD).
-template <int NB, bool GV = false, bool ANY = false>
+// A64: the vector array holds 4 GiB or more, rows are addressed with 64-bit offsets.
+template <int NB, bool GV = false, bool ANY = false, bool A64 = false>
 struct RegCacheT {
   static constexpr bool kInRegisters = true;
   static constexpr int kBestSlots = NB;
-#ifdef GGNN_PHASE_TIMING
-  uint32_t ph[12] = {0};
-  __device__ void flush_phases() {
-    if (lane_id() == 0)
-      for (int i = 0; i < 12; i++) atomicAdd(&g_phase_cycles[i], (unsigned long long)ph[i]);
-  }
-#endif
   u64 best[NB], pq;             // entry i: best[i / 64] of lane i % 64; kEmptyKey beyond the fill level
   int32_t B, P, nb, np;
   int32_t iter, max_iter;
@@ -414,14 +393,12 @@ struct RegCacheT {
   template <int DT, int NCH, int METRIC, int PASSES>
   __device__ void fetch(const GraphDev& G, int layer, int32_t p, const QueryRegs<DT, NCH>& q, int32_t excl_row) {
     const int lane = lane_id();
-    GGNN_T0();
     bool alive = p >= 0;
     int32_t row = -1;
     if (alive) {
       row = (layer == 0) ? p : G.to_base[layer][p];
       alive = row != excl_row;
     }
-    GGNN_TICK(1);  // adjacency row arrives
     const bool bit = maybe_listed(p);  // read alongside the first probe, not after the last (any p indexes the map)
     bool seen_rejected = false;
     if constexpr (GV) vis_fence();  // the popped id's entry is in the table (the adjacency row was awaited anyway)
@@ -430,7 +407,6 @@ struct RegCacheT {
       alive = kind == 0;
       seen_rejected = kind == 2;
     }
-    GGNN_TICK(2);  // hash probe
     // membership in best / prioq: only proposals whose bucket bit is set can be listed;
     // each of those is broadcast and compared with the entry every lane holds
     u64 cand = __ballot(alive && bit);
@@ -439,38 +415,29 @@ struct RegCacheT {
       const int j = __builtin_ctzll(cand);
       cand &= cand - 1;
       const int32_t pid = __builtin_amdgcn_readlane(p, j);
-#ifdef GGNN_PHASE_TIMING
-      ph[11]++;
-#endif
       bool hit = key_id(pq) == pid;
 #pragma unroll
       for (int e = 0; e < NB; e++) hit = hit || key_id(best[e]) == pid;
       if (__ballot(hit)) known |= 1ull << j;
     }
     alive = alive && !((known >> lane) & 1);
-    GGNN_TICK(3);  // membership in best / prioq
     const u64 mask = __ballot(alive);
     const int ns = __popcll(mask);
     // a point rejected before would be evaluated and rejected again: counted, not gathered
     evals += ns + __popcll(__ballot(seen_rejected));
     if (ns == 0) return;
     gathers += ns;
-#ifdef GGNN_PHASE_TIMING
-    ph[10] += (uint32_t)ns;
-#endif
     if (alive) {
       const int r = __popcll(mask & ((1ull << lane) - 1));
       surv_id[r] = p;
       surv_row[r] = row;
     }
     wave_sync();
-    GGNN_TICK(4);  // compaction
     // rows of one chunk per lane (128 bytes) cost four registers each: a third pass is in flight
     constexpr int RPP = RowSched<DT, PASSES>::rows_per_pass;
     constexpr int NP = (Elem<DT>::lanes == kRowLanes && NCH == 1) ? RowSched<DT, PASSES>::passes + 1 : RowSched<DT, PASSES>::passes;
-    for (int b0 = 0; b0 < ns; b0 += RPP * NP) gather_sum<DT, NCH, METRIC, NP>(G, q, surv_row, surv_d, b0, ns);
+    for (int b0 = 0; b0 < ns; b0 += RPP * NP) gather_sum<DT, NCH, METRIC, NP, !A64>(G, q, surv_row, surv_d, b0, ns);
     wave_sync();
-    GGNN_TICK(5);  // gather + distances
     // Alg. 2 Push, for the survivors in list order with the threshold re-evaluated after every push.
     // The threshold only shrinks, and only when a key enters best: the candidates that may enter
     // best are taken one by one, in order, and every lane notes the threshold in force when its own
@@ -487,9 +454,6 @@ struct RegCacheT {
       const int r = __builtin_ctzll(first);
       first &= first - 1;
       const u64 kr = read_lane_u64(key, r);
-#ifdef GGNN_PHASE_TIMING
-      ph[8]++;
-#endif
       if (key_d(kr) <= thr() && (nb < B || kr < last_best)) {
         best_insert(kr);
         refresh_bounds();
@@ -502,9 +466,6 @@ struct RegCacheT {
     const bool goes_in = ok && key < pq_last;
     u64 ins = __ballot(goes_in);
     const int m = __popcll(ins);
-#ifdef GGNN_PHASE_TIMING
-    ph[9] += (uint32_t)m;
-#endif
     if (m <= 2) {
       while (ins) {
         const int r = __builtin_ctzll(ins);
@@ -539,9 +500,7 @@ struct RegCacheT {
       const uint32_t h = listed_bucket(id);
       atomicOr(&listed_bits[h >> 5], 1u << (h & 31));
     }
-    GGNN_TICK(6);  // acceptance and pushes
     insert_rejected(mine && !ok, id);
-    GGNN_TICK(7);  // rejected filter
   }
 
   // the lists and counters of a search that continues in another launch

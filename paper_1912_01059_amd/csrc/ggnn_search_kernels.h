@@ -57,14 +57,15 @@ template <class C, int DT, int NCH, int METRIC, int PHASE>
 __device__ __forceinline__ void query_body(const GraphDev& G, const uint8_t* __restrict__ queries, int k,
                                            const SearchParams& sp, int every_layer, int32_t* __restrict__ ids,
                                            float* __restrict__ dists, uint32_t* __restrict__ counters,
-                                           const SplitBufs& sb) {
+                                           const SplitBufs& sb, int64_t first) {
   extern __shared__ __align__(16) unsigned char lds[];
   const int lane = lane_id();
-  int64_t qi = blockIdx.x;
+  int64_t qi = first + blockIdx.x;  // `first`: the launch's first workgroup within the batch (see chunk_blocks)
   if (PHASE == 2) {
     // XCD x takes part x of the sorted order: workgroup b is the (b / 8)-th of XCD b % 8
-    const int64_t i = (int64_t)(blockIdx.x % kXcds) * sb.per + blockIdx.x / kXcds;
-    if (blockIdx.x / kXcds >= (unsigned)sb.per || i >= sb.Q) return;
+    const int64_t b = qi;
+    const int64_t i = (b % kXcds) * sb.per + b / kXcds;
+    if (b / kXcds >= sb.per || i >= sb.Q) return;
     qi = sb.order[i];
   }
   C c;
@@ -106,9 +107,6 @@ __device__ __forceinline__ void query_body(const GraphDev& G, const uint8_t* __r
     return;
   }
   c.store_results(k, ids + (size_t)qi * k, dists + (size_t)qi * k);
-#ifdef GGNN_PHASE_TIMING
-  if constexpr (C::kInRegisters) c.flush_phases();
-#endif
   if (counters && lane == 0) {
     counters[4 * qi + 0] = c.n_pops();
     counters[4 * qi + 1] = c.n_evals();
@@ -121,8 +119,9 @@ __device__ __forceinline__ void query_body(const GraphDev& G, const uint8_t* __r
   template <class C, int DT, int NCH, int METRIC>                                                                   \
   __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(SearchWavesPerSimd<DT, NCH>::value))) void  \
   NAME(GraphDev G, const uint8_t* __restrict__ queries, int k, SearchParams sp, int every_layer,                    \
-       int32_t* __restrict__ ids, float* __restrict__ dists, uint32_t* __restrict__ counters, SplitBufs sb) {       \
-    query_body<C, DT, NCH, METRIC, PHASE>(G, queries, k, sp, every_layer, ids, dists, counters, sb);                \
+       int32_t* __restrict__ ids, float* __restrict__ dists, uint32_t* __restrict__ counters, SplitBufs sb,         \
+       int64_t first) {                                                                                             \
+    query_body<C, DT, NCH, METRIC, PHASE>(G, queries, k, sp, every_layer, ids, dists, counters, sb, first);         \
   }
 GGNN_QUERY_KERNEL(query_kernel, 0)
 GGNN_QUERY_KERNEL(query_upper_kernel, 1)
@@ -132,10 +131,10 @@ GGNN_QUERY_KERNEL(query_lower_kernel, 2)
 template <class C, int DT, int NCH, int METRIC>
 __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(SearchWavesPerSimd<DT, NCH>::value))) void merge_kernel(GraphDev G, int l_top, int l_m, SearchParams sp,
                                                       int32_t* __restrict__ out_rows, float* __restrict__ dnn1,
-                                                      unsigned long long* __restrict__ work) {
+                                                      unsigned long long* __restrict__ work, int64_t first) {
   extern __shared__ __align__(16) unsigned char lds[];
   const int lane = lane_id();
-  const int64_t z = blockIdx.x;
+  const int64_t z = first + blockIdx.x;
   C c;
   c.bind(lds, sp, z);
   c.init();
@@ -178,11 +177,11 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(SearchWav
 template <class C, int DT, int NCH, int METRIC>
 __global__ __launch_bounds__(kWave) void sym_search_kernel(GraphDev G, int layer, int round, float w_mid,
                                                            SearchParams sp, SymBuffers sb,
-                                                           unsigned long long* __restrict__ work) {
+                                                           unsigned long long* __restrict__ work, int64_t first) {
   extern __shared__ __align__(16) unsigned char lds[];
   constexpr int E = Elem<DT>::per_chunk;
   const int lane = lane_id();
-  const int64_t z = blockIdx.x;
+  const int64_t z = first + blockIdx.x;
   const int knn = G.K / 2, ksym = G.K - knn;
   const int32_t* __restrict__ Ed = G.edges[layer];
   if (lane == 0) sb.npref[z] = 0;
@@ -276,11 +275,13 @@ hipError_t launch_query_t(const GraphDev& G, int dtype, int metric, const void* 
                           const SearchParams& sp, int every_layer, int32_t* ids, float* dists, uint32_t* counters,
                           hipStream_t stream) {
   if (Q <= 0) return hipSuccess;
-  const dim3 grid((unsigned)Q);
   const size_t lds = C::lds_bytes(sp);
   constexpr int kU8Format = 3;
   const SplitBufs sb = {};
-  GGNN_DISPATCH(C, query_kernel, G, (const uint8_t*)queries, k, sp, every_layer, ids, dists, counters, sb);
+  for (int64_t first = 0; first < Q; first += kMaxBlocksPerLaunch) {
+    const dim3 grid(chunk_blocks(Q, first));
+    GGNN_DISPATCH(C, query_kernel, G, (const uint8_t*)queries, k, sp, every_layer, ids, dists, counters, sb, first);
+  }
   return hipGetLastError();
 }
 // one of the two launches of a large batch (sb.phase 1 or 2; register cache only)
@@ -289,34 +290,41 @@ hipError_t launch_query_split_t(const GraphDev& G, int dtype, int metric, const 
                                 const SearchParams& sp, int32_t* ids, float* dists, uint32_t* counters,
                                 const SplitBufs& sb, hipStream_t stream) {
   if (Q <= 0) return hipSuccess;
-  const dim3 grid((unsigned)(sb.phase == 2 ? (int64_t)kXcds * sb.per : Q));
+  const int64_t blocks = sb.phase == 2 ? (int64_t)kXcds * sb.per : Q;
   const size_t lds = C::lds_bytes(sp);
   constexpr int kU8Format = 3;
   const int every_layer = 1;
-  if (sb.phase == 1) {
-    GGNN_DISPATCH(C, query_upper_kernel, G, (const uint8_t*)queries, k, sp, every_layer, ids, dists, counters, sb);
-  } else {
-    GGNN_DISPATCH(C, query_lower_kernel, G, (const uint8_t*)queries, k, sp, every_layer, ids, dists, counters, sb);
+  for (int64_t first = 0; first < blocks; first += kMaxBlocksPerLaunch) {
+    const dim3 grid(chunk_blocks(blocks, first));
+    if (sb.phase == 1) {
+      GGNN_DISPATCH(C, query_upper_kernel, G, (const uint8_t*)queries, k, sp, every_layer, ids, dists, counters, sb, first);
+    } else {
+      GGNN_DISPATCH(C, query_lower_kernel, G, (const uint8_t*)queries, k, sp, every_layer, ids, dists, counters, sb, first);
+    }
   }
   return hipGetLastError();
 }
 template <class C>
 hipError_t launch_merge_t(const GraphDev& G, int dtype, int metric, int l_top, int l_m, const SearchParams& sp,
                           int32_t* out_rows, float* dnn1, unsigned long long* work, hipStream_t stream) {
-  const dim3 grid((unsigned)G.n[l_m]);
   const size_t lds = C::lds_bytes(sp);
   constexpr int kU8Format = 3;
-  GGNN_DISPATCH(C, merge_kernel, G, l_top, l_m, sp, out_rows, dnn1, work);
+  for (int64_t first = 0; first < G.n[l_m]; first += kMaxBlocksPerLaunch) {
+    const dim3 grid(chunk_blocks(G.n[l_m], first));
+    GGNN_DISPATCH(C, merge_kernel, G, l_top, l_m, sp, out_rows, dnn1, work, first);
+  }
   return hipGetLastError();
 }
 template <class C>
 hipError_t launch_sym_search_t(const GraphDev& G, int dtype, int metric, int layer, int round, float w_mid,
                                const SearchParams& sp, const SymBuffers& sb, unsigned long long* work,
                                hipStream_t stream) {
-  const dim3 grid((unsigned)G.n[layer]);
   const size_t lds = C::lds_bytes(sp);
   constexpr int kU8Format = 1;
-  GGNN_DISPATCH(C, sym_search_kernel, G, layer, round, w_mid, sp, sb, work);
+  for (int64_t first = 0; first < G.n[layer]; first += kMaxBlocksPerLaunch) {
+    const dim3 grid(chunk_blocks(G.n[layer], first));
+    GGNN_DISPATCH(C, sym_search_kernel, G, layer, round, w_mid, sp, sb, work, first);
+  }
   return hipGetLastError();
 }
 

@@ -11,7 +11,9 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libggnn.so")
-SOURCES = ["ggnn_search_reg.hip", "ggnn_search_split.hip", "ggnn_search_gv.hip", "ggnn_search_any.hip", "ggnn_search_lds.hip", "ggnn_build.hip", "ggnn_api.hip"]
+SOURCES = ["ggnn_search_reg.hip", "ggnn_search_reg_wide.hip", "ggnn_search_split.hip", "ggnn_search_split_wide.hip",
+           "ggnn_search_gv.hip", "ggnn_search_gv_wide.hip", "ggnn_search_any.hip", "ggnn_search_any_wide.hip",
+           "ggnn_search_lds.hip", "ggnn_build.hip", "ggnn_api.hip"]
 # -ffp-contract=off: float32 arithmetic is exactly what the source says (fused multiply-adds are
 # written out where they are wanted), which the bit-for-bit reproducible distances rely on.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
@@ -44,7 +46,7 @@ def _compile(args):
 def build(verbose: bool = False) -> str:
     hipcc = _hipcc()
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
+    with ThreadPoolExecutor(max_workers=min(len(SOURCES), os.cpu_count() or 4, 16)) as ex:
         objs = list(ex.map(_compile, [(hipcc, s) for s in SOURCES]))
     cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
     r = subprocess.run(cmd, capture_output=True, text=True)

@@ -49,9 +49,6 @@ def test_argument_errors_are_reported_without_a_gpu():
     assert b"too large" in L.ggnn_last_error()
     assert L.ggnn_graph_create(dummy, 1000, 130, 24, 3, 1, None, ctypes.byref(out)) == -1
     assert b"multiple of 16" in L.ggnn_last_error()
-    # vector arrays of 4 GiB or more are refused (rows are addressed with 32-bit byte offsets)
-    assert L.ggnn_graph_create(dummy, 8_388_608, 128, 24, 4, 1, None, ctypes.byref(out)) == -4
-    assert b"4 GiB" in L.ggnn_last_error()
 
 
 def test_missing_library_fails_loudly(monkeypatch):
