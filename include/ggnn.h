@@ -58,7 +58,9 @@ typedef enum {
 typedef struct {
   int32_t metric;         /* ggnn_metric [GGNN_L2]                                     */
   int32_t dtype;          /* ggnn_dtype of base and queries [GGNN_F32]                 */
-  int32_t segment_size;   /* s: points per segment and per top layer [32], <= 64       */
+  int32_t segment_size;   /* s: points per segment and per top layer [32], <= 64.  The paper asks
+                             for s > K/2; smaller s is accepted: rows then end in -1 until a merge
+                             from a higher layer fills them                             */
   float tau_build;        /* slack factor tau_b of the construction searches [0.5]     */
   int32_t refinements;    /* r refinement passes (Alg. 6) [2]; pass -1 for none        */
   int32_t pq_cap;         /* prioq capacity of the construction searches [64]          */
@@ -149,6 +151,24 @@ int ggnn_query_ex(const ggnn_graph* g, const void* queries_dev, int64_t Q, int32
                   int32_t pq_cap, int32_t visited_cap, int32_t max_iter, int32_t every_layer, void* stream,
                   int32_t* ids_dev, float* dists_dev, uint32_t* counters_dev, int32_t asynchronous);
 
+/* The same search with everything that steers its dispatch passed per call (a zero field selects the
+ * default; p may be NULL): nothing process-wide is read, so calls from several threads or streams do not
+ * interfere.  The ggnn_set_* calls at the end of this header set the process-wide defaults that ggnn_query,
+ * ggnn_query_ex and ggnn_query_from use instead. */
+typedef struct {
+  int32_t pq_cap, visited_cap, max_iter; /* as ggnn_query_ex                                               */
+  int32_t every_layer;                   /* 0: Sec. 4.4 shortcut, 1: every layer (Alg. 4)                  */
+  int32_t cache_mode;                    /* 0: best / prioq in registers when they fit, 1: always in LDS   */
+  int32_t global_visited_min_iter;       /* as ggnn_set_global_visited_threshold (0 default, < 0 never)    */
+  int64_t split_min_queries;             /* as ggnn_set_split_threshold (0 default, < 0 never two launches)*/
+  const int32_t* start_ids_dev;          /* as ggnn_query_from, or NULL                                    */
+  int32_t n_start;
+  int32_t asynchronous;
+  void* stream;                          /* hipStream_t, NULL = the graph's stream                         */
+} ggnn_query_params;
+int ggnn_query_with(const ggnn_graph* g, const void* queries_dev, int64_t Q, int32_t k, int32_t beam, float slack,
+                    const ggnn_query_params* p, int32_t* ids_dev, float* dists_dev, uint32_t* counters_dev);
+
 /* For callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc.  The every-layer search of ggnn_query_ex in its two-launch form
  * (upper layers; counting sort of the queries by the layer-1 point reached; bottom layer, one
@@ -210,7 +230,8 @@ int ggnn_graph_export_inv_count(const ggnn_graph* g, int32_t layer, int32_t* cou
 
 /* Where best and prioq live during a search: 0 (default) in registers whenever prioq holds at most
  * 64 entries and best at most 64 (128 for user queries), otherwise in LDS; 1 always in LDS.
- * Results do not depend on it.  Process-wide. */
+ * Results do not depend on it.  Process-wide default (an atomic; every call reads it once at entry);
+ * ggnn_query_with takes it per call. */
 int ggnn_set_cache_mode(int32_t mode);
 
 /* Batches of at least `min_queries` user queries that search every layer (register cache, three levels or
@@ -218,7 +239,7 @@ int ggnn_set_cache_mode(int32_t mode);
  * by the layer-1 point each arrived at, one contiguous part of that order per XCD, so that queries of
  * one region share an L2 cache.  Results and counters do not depend on it; the workspace comes from the
  * stream's memory pool (hipMallocAsync) and is returned to it.  Default 24576; 0 restores the default, a
- * value above every batch size turns the two-launch path off.  Process-wide. */
+ * value above every batch size turns the two-launch path off.  Process-wide default, as above. */
 int ggnn_set_split_threshold(int64_t min_queries);
 
 /* Where user queries keep their visited set.  By default (min_iter = 0) in LDS, except for batches
@@ -227,8 +248,7 @@ int ggnn_set_split_threshold(int64_t min_queries);
  * (taken from the stream's memory pool for the duration of the call), which is slower to probe but
  * leaves room for six wavefronts per SIMD.  min_iter > 0: global memory for every batch whose limit
  * is at least min_iter; min_iter < 0: always LDS.  Results and counters do not depend on it (Alg. 2
- * only asks that visited be exact).  Process-wide, not thread-safe against concurrent queries.
- * Returns GGNN_OK. */
+ * only asks that visited be exact).  Process-wide default, as above.  Returns GGNN_OK. */
 int ggnn_set_global_visited_threshold(int32_t min_iter);
 
 /* Measurement aid (not part of the method): gathers rows ids_dev[0..n_ids) (each in [0, n_rows), not

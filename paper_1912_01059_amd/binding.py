@@ -36,6 +36,12 @@ class GraphDesc(C.Structure):
                 ("dnn_mean", C.c_float), ("dnn_max", C.c_float), ("graph_bytes", C.c_int64), ("seed", C.c_uint64)]
 
 
+class QueryParams(C.Structure):
+    _fields_ = [("pq_cap", C.c_int32), ("visited_cap", C.c_int32), ("max_iter", C.c_int32), ("every_layer", C.c_int32),
+                ("cache_mode", C.c_int32), ("global_visited_min_iter", C.c_int32), ("split_min_queries", C.c_int64),
+                ("start_ids_dev", C.c_void_p), ("n_start", C.c_int32), ("asynchronous", C.c_int32), ("stream", C.c_void_p)]
+
+
 class BuildTimes(C.Structure):
     _fields_ = [("merge_ms", C.c_float), ("sym_ms", C.c_float), ("select_ms", C.c_float),
                 ("stats_ms", C.c_float), ("total_ms", C.c_float), ("merge_pops", C.c_uint64),
@@ -44,7 +50,7 @@ class BuildTimes(C.Structure):
 
 EXPORTS = [
     "ggnn_build", "ggnn_build_ex", "ggnn_graph_create", "ggnn_select", "ggnn_merge", "ggnn_sym",
-    "ggnn_build_steps", "ggnn_build_get_times", "ggnn_query", "ggnn_query_ex", "ggnn_query_static", "ggnn_query_from", "ggnn_graph_info",
+    "ggnn_build_steps", "ggnn_build_get_times", "ggnn_query", "ggnn_query_ex", "ggnn_query_with", "ggnn_query_static", "ggnn_query_from", "ggnn_graph_info",
     "ggnn_graph_export", "ggnn_graph_import", "ggnn_graph_export_dnn", "ggnn_graph_import_dnn",
     "ggnn_graph_export_inv_count", "ggnn_set_cache_mode", "ggnn_set_split_threshold", "ggnn_set_global_visited_threshold", "ggnn_gather_probe", "ggnn_merge_shards", "ggnn_free", "ggnn_last_error",
 ]
@@ -69,6 +75,7 @@ def lib():
         L.ggnn_build_get_times.argtypes = [vp, C.POINTER(BuildTimes)]
         L.ggnn_query.argtypes = [vp, vp, i64, i32, i32, f32, vp, vp]
         L.ggnn_query_ex.argtypes = [vp, vp, i64, i32, i32, f32, i32, i32, i32, i32, vp, vp, vp, vp, i32]
+        L.ggnn_query_with.argtypes = [vp, vp, i64, i32, i32, f32, C.POINTER(QueryParams), vp, vp, vp]
         L.ggnn_query_static.argtypes = [vp, vp, i64, i32, i32, f32, i32, i32, i32, vp, vp, vp, vp, i32]
         L.ggnn_query_from.argtypes = [vp, vp, i64, i32, i32, f32, i32, i32, i32, vp, i32, vp, vp, vp, vp, i32]
         L.ggnn_graph_info.argtypes = [vp, C.POINTER(GraphDesc)]
@@ -218,6 +225,7 @@ class Graph:
         d = GraphDesc()
         _check(lib().ggnn_graph_info(self.h, C.byref(d)))
         self.N, self.D, self.K, self.L, self.s, self.g = d.N, d.D, d.K, d.L, d.s, d.g
+        self.dtype, self.metric = d.dtype, d.metric
         self.n = [d.n[l] for l in range(d.L)]
         self.graph_bytes = d.graph_bytes
 
@@ -282,9 +290,9 @@ class Graph:
         return c
 
     def query(self, queries, k, beam, slack, pq_cap=0, visited_cap=0, max_iter=0, every_layer=False,
-              counters=False, out=None, stream=None, asynchronous=False, start_ids=None):
+              counters=False, out=None, stream=None, asynchronous=False, start_ids=None, **tuning):
         return query(self, queries, k, beam, slack, pq_cap, visited_cap, max_iter, every_layer, counters, out,
-                     stream, asynchronous, start_ids)
+                     stream, asynchronous, start_ids, **tuning)
 
 
 def query_static(graph, queries, k, beam, slack, out, pq_cap=0, visited_cap=0, max_iter=0, counters=None,
@@ -292,6 +300,7 @@ def query_static(graph, queries, k, beam, slack, out, pq_cap=0, visited_cap=0, m
     """ggnn_query_static: the every-layer search with the library's static workspace.  Nothing is allocated
     here either: `out` = (ids, dists) and, optionally, `counters` (Q x 4 int32) are the caller's tensors."""
     import torch
+    _check_query_tensors(graph, queries, k, out, None, counters)
     ids, dists = out
     if stream is None:
         stream = torch.cuda.current_stream().cuda_stream
@@ -319,10 +328,48 @@ def build(base, K, levels, seed=42, metric=L2, segment_size=0, tau_build=0.0, re
     return Graph(h, base)
 
 
-def query(graph, queries, k, beam, slack, pq_cap=0, visited_cap=0, max_iter=0, every_layer=False,
-          counters=False, out=None, stream=None, asynchronous=False, start_ids=None):
-    """ggnn_query_ex.  Returns (ids, dists[, counters]) as GPU tensors; `out` = (ids, dists) reuses buffers."""
+def _check_query_tensors(graph, queries, k, out, start_ids, counters=None):
+    """The kernels stride the query array by the graph's row length and trust every pointer: shapes, element
+    types and devices are checked here, before anything is launched."""
     import torch
+    want = torch.uint8 if (graph.dtype == U8 and graph.metric == L2) else torch.float32
+    if graph.metric == COSINE and graph.dtype != F32:
+        raise TypeError("a cosine graph takes float32 queries")
+    if not isinstance(queries, torch.Tensor) or not queries.is_cuda:
+        raise TypeError("queries must be a GPU tensor")
+    if queries.dim() != 2 or queries.shape[1] != graph.D:
+        raise GgnnError("queries must have shape (Q, %d), got %s" % (graph.D, tuple(queries.shape)))
+    if queries.dtype != want:
+        raise TypeError("queries must be %s like the graph's rows, got %s" % (want, queries.dtype))
+    if not queries.is_contiguous():
+        raise GgnnError("queries must be contiguous")
+    Q = queries.shape[0]
+    if k < 1:
+        raise GgnnError("k must be positive")
+    if out is not None:
+        ids, dists = out
+        for t, dt, name in ((ids, torch.int32, "ids"), (dists, torch.float32, "dists")):
+            if not isinstance(t, torch.Tensor) or t.device != queries.device or t.dtype != dt or tuple(t.shape) != (Q, k) \
+                    or not t.is_contiguous():
+                raise GgnnError("out %s must be a contiguous %s tensor of shape (%d, %d) on %s" % (name, dt, Q, k, queries.device))
+    if counters is not None:
+        if not isinstance(counters, torch.Tensor) or counters.device != queries.device or counters.dtype != torch.int32 \
+                or tuple(counters.shape) != (Q, 4) or not counters.is_contiguous():
+            raise GgnnError("counters must be a contiguous int32 tensor of shape (%d, 4) on %s" % (Q, queries.device))
+    if start_ids is not None:
+        if not isinstance(start_ids, torch.Tensor) or start_ids.device != queries.device or start_ids.dtype != torch.int32 \
+                or start_ids.dim() != 1 or not start_ids.is_contiguous():
+            raise GgnnError("start_ids must be a contiguous 1-D int32 tensor on %s" % (queries.device,))
+
+
+def query(graph, queries, k, beam, slack, pq_cap=0, visited_cap=0, max_iter=0, every_layer=False,
+          counters=False, out=None, stream=None, asynchronous=False, start_ids=None, cache_mode=None,
+          split_threshold=None, global_visited=None):
+    """ggnn_query_ex (ggnn_query_from with start_ids).  Returns (ids, dists[, counters]) as GPU tensors; `out` =
+    (ids, dists) reuses buffers.  cache_mode / split_threshold / global_visited: when any is given the call goes
+    through ggnn_query_with, which takes them per call instead of from the process-wide defaults."""
+    import torch
+    _check_query_tensors(graph, queries, k, out, start_ids)
     Q = queries.shape[0]
     if out is None:
         ids = torch.empty((Q, k), dtype=torch.int32, device=queries.device)
@@ -332,6 +379,18 @@ def query(graph, queries, k, beam, slack, pq_cap=0, visited_cap=0, max_iter=0, e
     cnt = torch.zeros((Q, 4), dtype=torch.int32, device=queries.device) if counters else None
     if stream is None:
         stream = torch.cuda.current_stream().cuda_stream
+    if cache_mode is not None or split_threshold is not None or global_visited is not None:
+        p = QueryParams()
+        p.pq_cap, p.visited_cap, p.max_iter, p.every_layer = pq_cap, visited_cap, max_iter, 1 if every_layer else 0
+        p.cache_mode = cache_mode or 0
+        p.split_min_queries = split_threshold or 0
+        p.global_visited_min_iter = global_visited or 0
+        p.start_ids_dev = start_ids.data_ptr() if start_ids is not None else None
+        p.n_start = start_ids.shape[0] if start_ids is not None else 0
+        p.asynchronous, p.stream = (1 if asynchronous else 0), stream
+        _check(lib().ggnn_query_with(graph.h, _dev_ptr(queries), Q, k, beam, slack, C.byref(p), _dev_ptr(ids), _dev_ptr(dists),
+                                     _dev_ptr(cnt) if counters else None))
+        return (ids, dists, cnt) if counters else (ids, dists)
     if start_ids is not None:  # ggnn_query_from: bottom layer only, from the given start points
         _check(lib().ggnn_query_from(graph.h, _dev_ptr(queries), Q, k, beam, slack, pq_cap, visited_cap, max_iter,
                                      _dev_ptr(start_ids), start_ids.shape[0], C.c_void_p(stream), _dev_ptr(ids),

@@ -5,6 +5,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <atomic>
 #include <mutex>
 #include <new>
 #include <vector>
@@ -63,7 +64,40 @@ int scratch_ptr(unsigned char** out) {
 }
 
 constexpr size_t kMaxLds = 160 * 1024;  // LDS of a compute unit on gfx950, all of which one workgroup may take
-int g_cache_mode = 0;  // 0: registers whenever best and prioq fit 64 entries, 1: always LDS
+
+// How a search is dispatched.  Every call works on a snapshot of its own, taken once at the entry point
+// (from the caller's ggnn_query_params, or from the process-wide defaults behind the ggnn_set_* calls,
+// which are atomics): nothing on the dispatch path reads shared mutable state.
+struct Tuning {
+  int cache_mode;        // 0: best / prioq in registers whenever they fit, 1: always in LDS
+  int64_t split_min;     // batches of at least this many every-layer queries take two launches
+  int32_t vis_min_iter;  // iteration limit from which visited moves to global memory; <= 0: never
+  bool vis_forced;       // ... whatever the batch size
+};
+constexpr int64_t kSplitMinQueries = 24576;  // smaller batches gain nothing from the two-launch path
+constexpr int32_t kVisGlobalMinIter = 1100;
+std::atomic<int> g_cache_mode{0};
+std::atomic<int64_t> g_split_min_queries{kSplitMinQueries};
+std::atomic<int32_t> g_vis_global_min_iter{kVisGlobalMinIter};
+std::atomic<bool> g_vis_global_forced{false};
+Tuning process_tuning() {
+  return Tuning{g_cache_mode.load(), g_split_min_queries.load(), g_vis_global_min_iter.load(), g_vis_global_forced.load()};
+}
+
+// compute units of the current device (looked up once per device)
+std::atomic<int> g_cu_count[64];
+int cu_count() {
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  cus = g_cu_count[dev].load();
+  if (cus > 0) return cus;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) {
+    (void)hipGetLastError();
+    cus = 256;
+  }
+  g_cu_count[dev].store(cus);
+  return cus;
+}
 
 int next_pow2(int v) {
   int p = 1;
@@ -124,13 +158,14 @@ GraphDev device_view(const ggnn_graph* g) {
 int row_dtype(const ggnn_graph* g) { return g->norm ? GGNN_F32 : g->dtype; }
 
 // where the lists of a search live: 1 / 2 = registers with best in one / two registers per lane, 0 = LDS
-int register_slots(const SearchParams& sp, bool user_query) {
-  if (g_cache_mode != 0 || sp.P > kWave) return 0;
+int register_slots(const SearchParams& sp, bool user_query, const Tuning& t) {
+  if (t.cache_mode != 0 || sp.P > kWave) return 0;
   if (sp.B <= kWave) return 1;
   return (user_query && sp.B <= 2 * kWave) ? 2 : 0;
 }
 
-int make_search_params(int B, int P, int V, int max_iter, float tau, float dnn, SearchParams* sp, bool user_query = false) {
+int make_search_params(int B, int P, int V, int max_iter, float tau, float dnn, SearchParams* sp, const Tuning& t,
+                       bool user_query = false) {
   if (B < 1 || P < 1 || V < 1 || max_iter < 0) return fail(GGNN_ERR_INVALID, "cache capacities must be positive");
   if (max_iter > V) return fail(GGNN_ERR_INVALID, "max_iter (%d) must not exceed visited_cap (%d)", max_iter, V);
   sp->B = B; sp->P = P; sp->max_iter = max_iter;
@@ -138,7 +173,7 @@ int make_search_params(int B, int P, int V, int max_iter, float tau, float dnn, 
   if (sp->H < 64) sp->H = 64;
   sp->tau = tau; sp->dnn = dnn;
   sp->start = nullptr; sp->n_start = 0; sp->vis = nullptr;
-  const int slots = register_slots(*sp, user_query);
+  const int slots = register_slots(*sp, user_query, t);
   const size_t need = slots == 1 ? RegCache::lds_bytes(*sp) : slots == 2 ? RegCache2::lds_bytes(*sp) : LdsCache::lds_bytes(*sp);
   if (need > kMaxLds)
     return fail(GGNN_ERR_LIMIT, "cache of best=%d prioq=%d visited=%d needs %zu bytes of LDS, limit %zu", B, P, V,
@@ -148,8 +183,8 @@ int make_search_params(int B, int P, int V, int max_iter, float tau, float dnn, 
 
 hipError_t launch_query_whole(const GraphDev& G, int dtype, int metric, const void* queries, int64_t Q, int k,
                               const SearchParams& sp, int every_layer, int32_t* ids, float* dists, uint32_t* counters,
-                              hipStream_t stream) {
-  const int slots = register_slots(sp, true);
+                              hipStream_t stream, const Tuning& t) {
+  const int slots = register_slots(sp, true, t);
   // beyond 384 iterations a power-of-two table would be larger than 1024 slots: size it to the limit
   const bool wide = !G.addr32;  // arrays of 4 GiB and more: the variants with 64-bit row offsets
   if (slots >= 1 && 2 * sp.max_iter + 256 > 1024)
@@ -158,14 +193,6 @@ hipError_t launch_query_whole(const GraphDev& G, int dtype, int metric, const vo
   if (slots == 2) return (wide ? launch_query_reg2_wide : launch_query_reg2)(G, dtype, metric, queries, Q, k, sp, every_layer, ids, dists, counters, stream);
   return launch_query_lds(G, dtype, metric, queries, Q, k, sp, every_layer, ids, dists, counters, stream);
 }
-
-// Batches of this many queries and more are answered in two launches with the bottom-layer searches
-// ordered by region (see SplitBufs); smaller ones gain nothing from it.
-constexpr int64_t kSplitMinQueries = 24576;
-int64_t g_split_min_queries = kSplitMinQueries;
-constexpr int32_t kVisGlobalMinIter = 1100;  // iteration limit from which user queries keep visited in global memory
-int32_t g_vis_global_min_iter = kVisGlobalMinIter;
-bool g_vis_global_forced = false;  // set through ggnn_set_global_visited_threshold: applies whatever the batch size
 
 // Workspace of the two-launch path: the lists put aside after the upper layers (state), counters
 // (meta), the sort keys, the sorted order and the bins of the counting sort.
@@ -213,14 +240,13 @@ hipError_t launch_query_two(const GraphDev& G, int dtype, int metric, const void
 
 hipError_t launch_query(const GraphDev& G, int dtype, int metric, const void* queries, int64_t Q, int k,
                         const SearchParams& sp, int every_layer, int32_t* ids, float* dists, uint32_t* counters,
-                        hipStream_t stream) {
-  const int slots = register_slots(sp, true);
-  // wavefronts the GPU holds at once when the visited table is in LDS (256 compute units, at most 24
-  // wavefronts each): a batch that fits gains nothing from a table in global memory, which is slower to probe
+                        hipStream_t stream, const Tuning& t) {
+  const int slots = register_slots(sp, true, t);
+  // wavefronts the GPU holds at once when the visited table is in LDS (at most 24 per compute unit): a
+  // batch that fits gains nothing from a table in global memory, which is slower to probe
   const size_t lds_table = slots == 2 ? RegCache2Any::lds_bytes(sp) : RegCacheAny::lds_bytes(sp);
-  const int64_t resident = 256 * (int64_t)(kMaxLds / lds_table < 24 ? kMaxLds / lds_table : 24);
-  if (slots >= 1 && g_vis_global_min_iter > 0 && sp.max_iter >= g_vis_global_min_iter &&
-      (Q > resident || g_vis_global_forced)) {
+  const int64_t resident = (int64_t)cu_count() * (int64_t)(kMaxLds / lds_table < 24 ? kMaxLds / lds_table : 24);
+  if (slots >= 1 && t.vis_min_iter > 0 && sp.max_iter >= t.vis_min_iter && (Q > resident || t.vis_forced)) {
     // long searches: one visited table per query in global memory, from the stream's memory pool
     const size_t bytes = (size_t)Q * (size_t)RegCacheGV::vis_slots(sp.max_iter) * sizeof(int32_t);
     int32_t* vis = nullptr;
@@ -233,47 +259,60 @@ hipError_t launch_query(const GraphDev& G, int dtype, int metric, const void* qu
     }
     (void)hipGetLastError();  // no workspace: the table stays in LDS
   }
-  const bool split = every_layer && G.L >= 3 && !sp.start && slots >= 1 && Q >= g_split_min_queries;
-  if (!split) return launch_query_whole(G, dtype, metric, queries, Q, k, sp, every_layer, ids, dists, counters, stream);
+  const bool split = every_layer && G.L >= 3 && !sp.start && slots >= 1 && Q >= t.split_min;
+  if (!split) return launch_query_whole(G, dtype, metric, queries, Q, k, sp, every_layer, ids, dists, counters, stream, t);
   // workspace from the stream's memory pool
   const SplitLayout lay = split_layout(G, slots, Q);
   unsigned char* ws = nullptr;
   if (hipMallocAsync((void**)&ws, lay.total, stream) != hipSuccess) {
     (void)hipGetLastError();  // no workspace: the one-launch path needs none
-    return launch_query_whole(G, dtype, metric, queries, Q, k, sp, every_layer, ids, dists, counters, stream);
+    return launch_query_whole(G, dtype, metric, queries, Q, k, sp, every_layer, ids, dists, counters, stream, t);
   }
   const hipError_t e = launch_query_two(G, dtype, metric, queries, Q, k, sp, slots, ids, dists, counters, ws, lay, stream);
   const hipError_t f = hipFreeAsync(ws, stream);
   return e != hipSuccess ? e : f;
 }
 hipError_t launch_merge(const GraphDev& G, int dtype, int metric, int l_top, int l_m, const SearchParams& sp,
-                        int32_t* out_rows, float* dnn1, unsigned long long* work, hipStream_t stream) {
-  if (register_slots(sp, false) != 1) return launch_merge_lds(G, dtype, metric, l_top, l_m, sp, out_rows, dnn1, work, stream);
+                        int32_t* out_rows, float* dnn1, unsigned long long* work, hipStream_t stream, const Tuning& t) {
+  if (register_slots(sp, false, t) != 1) return launch_merge_lds(G, dtype, metric, l_top, l_m, sp, out_rows, dnn1, work, stream);
   return (G.addr32 ? launch_merge_reg : launch_merge_reg_wide)(G, dtype, metric, l_top, l_m, sp, out_rows, dnn1, work, stream);
 }
 hipError_t launch_sym_search(const GraphDev& G, int dtype, int metric, int layer, int round, float w_mid,
                              const SearchParams& sp, const SymBuffers& sb, unsigned long long* work,
-                             hipStream_t stream) {
-  if (register_slots(sp, false) != 1) return launch_sym_search_lds(G, dtype, metric, layer, round, w_mid, sp, sb, work, stream);
+                             hipStream_t stream, const Tuning& t) {
+  if (register_slots(sp, false, t) != 1) return launch_sym_search_lds(G, dtype, metric, layer, round, w_mid, sp, sb, work, stream);
   return (G.addr32 ? launch_sym_search_reg : launch_sym_search_reg_wide)(G, dtype, metric, layer, round, w_mid, sp, sb, work, stream);
 }
 
+void release_sym_buffers(ggnn_graph* g);
 int ensure_sym_buffers(ggnn_graph* g) {
   if (g->sb_ready) return GGNN_OK;
   const int64_t n = g->n[0];
   const int ksym = g->K - g->K / 2;
   SymBuffers& sb = g->sb;
-  HIP_TRY(hipMalloc(&sb.inv, sizeof(int32_t) * n * ksym));
-  HIP_TRY(hipMalloc(&sb.ninv, sizeof(int32_t) * n));
-  HIP_TRY(hipMalloc(&sb.pref, sizeof(u64) * n * g->K));
-  HIP_TRY(hipMalloc(&sb.npref, sizeof(int32_t) * n));
-  HIP_TRY(hipMalloc(&sb.ptr, sizeof(int32_t) * n));
-  HIP_TRY(hipMalloc(&sb.state, sizeof(int32_t) * n));
-  HIP_TRY(hipMalloc(&sb.hold, sizeof(int32_t) * n * ksym));
-  HIP_TRY(hipMalloc(&sb.nhold, sizeof(int32_t) * n));
-  HIP_TRY(hipMalloc(&sb.head, sizeof(int32_t) * n));
-  HIP_TRY(hipMalloc(&sb.next, sizeof(int32_t) * n));
-  HIP_TRY(hipMalloc(&sb.pending, sizeof(int32_t)));
+  sb = SymBuffers{};
+  const hipError_t e = [&]() -> hipError_t {
+    hipError_t r;
+#define SYM_ALLOC(field, bytes) \
+    if ((r = hipMalloc(&sb.field, (bytes))) != hipSuccess) return r
+    SYM_ALLOC(inv, sizeof(int32_t) * n * ksym);
+    SYM_ALLOC(ninv, sizeof(int32_t) * n);
+    SYM_ALLOC(pref, sizeof(u64) * n * g->K);
+    SYM_ALLOC(npref, sizeof(int32_t) * n);
+    SYM_ALLOC(ptr, sizeof(int32_t) * n);
+    SYM_ALLOC(state, sizeof(int32_t) * n);
+    SYM_ALLOC(hold, sizeof(int32_t) * n * ksym);
+    SYM_ALLOC(nhold, sizeof(int32_t) * n);
+    SYM_ALLOC(head, sizeof(int32_t) * n);
+    SYM_ALLOC(next, sizeof(int32_t) * n);
+    SYM_ALLOC(pending, sizeof(int32_t));
+#undef SYM_ALLOC
+    return hipSuccess;
+  }();
+  if (e != hipSuccess) {
+    release_sym_buffers(g);  // what was allocated before the failure is returned
+    return fail(e == hipErrorOutOfMemory ? GGNN_ERR_MEMORY : GGNN_ERR_HIP, "buffers of the symmetric linking: %s", hipGetErrorString(e));
+  }
   g->sb_ready = true;
   return GGNN_OK;
 }
@@ -337,19 +376,19 @@ int ggnn_gather_probe(const void* rows_dev, int64_t n_rows, int32_t row_bytes, c
 
 int ggnn_set_cache_mode(int32_t mode) {
   if (mode != 0 && mode != 1) return fail(GGNN_ERR_INVALID, "cache mode %d is neither 0 nor 1", mode);
-  g_cache_mode = mode;
+  g_cache_mode.store(mode);
   return GGNN_OK;
 }
 
 int ggnn_set_split_threshold(int64_t min_queries) {
   if (min_queries < 0) return fail(GGNN_ERR_INVALID, "min_queries = %lld is negative", (long long)min_queries);
-  g_split_min_queries = min_queries == 0 ? kSplitMinQueries : min_queries;
+  g_split_min_queries.store(min_queries == 0 ? kSplitMinQueries : min_queries);
   return GGNN_OK;
 }
 
 int ggnn_set_global_visited_threshold(int32_t min_iter) {
-  g_vis_global_min_iter = min_iter == 0 ? kVisGlobalMinIter : min_iter;  // negative: never
-  g_vis_global_forced = min_iter > 0;
+  g_vis_global_min_iter.store(min_iter == 0 ? kVisGlobalMinIter : min_iter);  // negative: never
+  g_vis_global_forced.store(min_iter > 0);
   return GGNN_OK;
 }
 
@@ -405,7 +444,7 @@ int ggnn_graph_create(const void* base_dev, int64_t N, int32_t D, int32_t K, int
     return fail(GGNN_ERR_INVALID, "bottom segments would hold more than 64 points");
   }
   SearchParams sp;
-  int rc = make_search_params(K, g->pq_cap, g->visited_cap, g->max_iter, g->tau_build, 0.0f, &sp);
+  int rc = make_search_params(K, g->pq_cap, g->visited_cap, g->max_iter, g->tau_build, 0.0f, &sp, process_tuning());
   if (rc != GGNN_OK) { delete g; return rc; }
 
 #define CREATE_TRY(expr)                                                                   \
@@ -463,12 +502,13 @@ int ggnn_merge(ggnn_graph* g, int32_t l_top, int32_t l_m) {
     return fail(GGNN_ERR_INVALID, "merge(%d, %d) outside the hierarchy", l_top, l_m);
   SearchParams sp;
   // during construction the mean first-neighbour distance stands in for the maximum (Eq. 4)
-  int rc = make_search_params(g->K, g->pq_cap, g->visited_cap, g->max_iter, g->tau_build, g->stats[0], &sp);
+  const Tuning tune = process_tuning();
+  int rc = make_search_params(g->K, g->pq_cap, g->visited_cap, g->max_iter, g->tau_build, g->stats[0], &sp, tune);
   if (rc != GGNN_OK) return rc;
   {
     PhaseTimer t(g->stream);
     GraphDev G = device_view(g);
-    HIP_TRY(launch_merge(G, row_dtype(g), g->metric, l_top, l_m, sp, g->edge_tmp, g->dnn1, g->work_dev, g->stream));
+    HIP_TRY(launch_merge(G, row_dtype(g), g->metric, l_top, l_m, sp, g->edge_tmp, g->dnn1, g->work_dev, g->stream, tune));
     // the buffer becomes the layer (inverse links of the layer are thereby discarded)
     HIP_TRY(hipMemcpyAsync(g->edges[l_m], g->edge_tmp, sizeof(int32_t) * g->n[l_m] * g->K, hipMemcpyDeviceToDevice, g->stream));
     HIP_TRY(launch_fill_i32(g->inv_count[l_m], g->n[l_m], 0, g->stream));
@@ -491,7 +531,8 @@ int ggnn_sym(ggnn_graph* g, int32_t layer) {
   int rc = ensure_sym_buffers(g);
   if (rc != GGNN_OK) return rc;
   SearchParams sp;
-  rc = make_search_params(g->K, g->pq_cap, g->visited_cap, g->max_iter, g->tau_build, g->stats[0], &sp);
+  const Tuning tune = process_tuning();
+  rc = make_search_params(g->K, g->pq_cap, g->visited_cap, g->max_iter, g->tau_build, g->stats[0], &sp, tune);
   if (rc != GGNN_OK) return rc;
   PhaseTimer t(g->stream);
   GraphDev G = device_view(g);
@@ -502,14 +543,20 @@ int ggnn_sym(ggnn_graph* g, int32_t layer) {
   HIP_TRY(launch_fill_i32(sb.nhold, n, 0, g->stream));
   HIP_TRY(launch_fill_i32(sb.head, n, -1, g->stream));
   for (int round = 0; round < knn; round++) {
-    HIP_TRY(launch_sym_search(G, row_dtype(g), g->metric, layer, round, g->w_mid, sp, sb, g->work_dev, g->stream));
+    HIP_TRY(launch_sym_search(G, row_dtype(g), g->metric, layer, round, g->w_mid, sp, sb, g->work_dev, g->stream, tune));
+    // propose / resolve until a resolve pass turns nobody away.  The host looks at the count of the
+    // last of kSymRoundsPerCheck passes only: once a pass has no losers nobody is proposing any more, so
+    // the passes after it change nothing and count nothing.
+    constexpr int kSymRoundsPerCheck = 4;
     bool first = true;
     for (;;) {
-      HIP_TRY(launch_fill_i32(sb.pending, 1, 0, g->stream));
-      if (first) HIP_TRY(launch_sym_propose_first(G, layer, sb, sp.B, g->stream));
-      else HIP_TRY(launch_sym_propose(G, layer, sb, sp.B, g->stream));
-      first = false;
-      HIP_TRY(launch_sym_resolve(G, layer, sb, sp.B, g->stream));
+      for (int i = 0; i < kSymRoundsPerCheck; i++) {
+        HIP_TRY(launch_fill_i32(sb.pending, 1, 0, g->stream));
+        if (first) HIP_TRY(launch_sym_propose_first(G, layer, sb, sp.B, g->stream));
+        else HIP_TRY(launch_sym_propose(G, layer, sb, sp.B, g->stream));
+        first = false;
+        HIP_TRY(launch_sym_resolve(G, layer, sb, sp.B, g->stream));
+      }
       int32_t pending = 0;
       HIP_TRY(hipMemcpyAsync(&pending, sb.pending, sizeof(int32_t), hipMemcpyDeviceToHost, g->stream));
       HIP_TRY(hipStreamSynchronize(g->stream));
@@ -581,7 +628,7 @@ int ggnn_build_get_times(const ggnn_graph* g, ggnn_build_times* out) {
 static int query_impl(const ggnn_graph* g, const void* queries_dev, int64_t Q, int32_t k, int32_t beam, float slack,
                       int32_t pq_cap, int32_t visited_cap, int32_t max_iter, int32_t every_layer,
                       const int32_t* start_ids_dev, int32_t n_start, void* stream, int32_t* ids_dev, float* dists_dev,
-                      uint32_t* counters_dev, int32_t asynchronous) {
+                      uint32_t* counters_dev, int32_t asynchronous, const Tuning& tune) {
   if (!g) return fail(GGNN_ERR_INVALID, "graph is NULL");
   if (Q < 0 || Q > 0x7FFFFFFFll) return fail(GGNN_ERR_INVALID, "Q = %lld outside [0, 2^31)", (long long)Q);
   if (Q == 0) return GGNN_OK;
@@ -595,7 +642,7 @@ static int query_impl(const ggnn_graph* g, const void* queries_dev, int64_t Q, i
   const int it = max_iter > 0 ? max_iter : V;
   SearchParams sp;
   // user queries bound the slack by the maximum first-neighbour distance (Eq. 2, Eq. 3)
-  int rc = make_search_params(B, P, V, it, slack, g->stats[1], &sp, true);
+  int rc = make_search_params(B, P, V, it, slack, g->stats[1], &sp, tune, true);
   if (rc != GGNN_OK) return rc;
   hipStream_t st = stream ? (hipStream_t)stream : g->stream;
   if (start_ids_dev) {
@@ -614,7 +661,7 @@ static int query_impl(const ggnn_graph* g, const void* queries_dev, int64_t Q, i
   GraphDev G = device_view(g);
   if (g->metric == GGNN_COSINE && g->dtype != GGNN_F32) return fail(GGNN_ERR_INVALID, "cosine needs float32 queries");
   HIP_TRY(launch_query(G, row_dtype(g), g->metric, queries_dev, Q, k, sp, every_layer ? 1 : 0, ids_dev, dists_dev,
-                       counters_dev, st));
+                       counters_dev, st, tune));
   if (!asynchronous) HIP_TRY(hipStreamSynchronize(st));
   return GGNN_OK;
 }
@@ -623,7 +670,24 @@ int ggnn_query_ex(const ggnn_graph* g, const void* queries_dev, int64_t Q, int32
                   int32_t pq_cap, int32_t visited_cap, int32_t max_iter, int32_t every_layer, void* stream,
                   int32_t* ids_dev, float* dists_dev, uint32_t* counters_dev, int32_t asynchronous) {
   return query_impl(g, queries_dev, Q, k, beam, slack, pq_cap, visited_cap, max_iter, every_layer, nullptr, 0, stream,
-                    ids_dev, dists_dev, counters_dev, asynchronous);
+                    ids_dev, dists_dev, counters_dev, asynchronous, process_tuning());
+}
+
+int ggnn_query_with(const ggnn_graph* g, const void* queries_dev, int64_t Q, int32_t k, int32_t beam, float slack,
+                    const ggnn_query_params* p, int32_t* ids_dev, float* dists_dev, uint32_t* counters_dev) {
+  ggnn_query_params dflt;
+  memset(&dflt, 0, sizeof(dflt));
+  if (!p) p = &dflt;
+  if (p->cache_mode != 0 && p->cache_mode != 1) return fail(GGNN_ERR_INVALID, "cache_mode %d is neither 0 nor 1", p->cache_mode);
+  Tuning tune;
+  tune.cache_mode = p->cache_mode;
+  tune.split_min = p->split_min_queries == 0 ? kSplitMinQueries : (p->split_min_queries < 0 ? INT64_MAX : p->split_min_queries);
+  tune.vis_min_iter = p->global_visited_min_iter == 0 ? kVisGlobalMinIter : p->global_visited_min_iter;
+  tune.vis_forced = p->global_visited_min_iter > 0;
+  if (p->start_ids_dev == nullptr && p->n_start != 0) return fail(GGNN_ERR_INVALID, "n_start = %d without start_ids_dev", p->n_start);
+  return query_impl(g, queries_dev, Q, k, beam, slack, p->pq_cap, p->visited_cap, p->max_iter,
+                    p->start_ids_dev ? 0 : p->every_layer, p->start_ids_dev, p->n_start, p->stream, ids_dev, dists_dev,
+                    counters_dev, p->asynchronous, tune);
 }
 
 int ggnn_query_from(const ggnn_graph* g, const void* queries_dev, int64_t Q, int32_t k, int32_t beam, float slack,
@@ -631,7 +695,7 @@ int ggnn_query_from(const ggnn_graph* g, const void* queries_dev, int64_t Q, int
                     void* stream, int32_t* ids_dev, float* dists_dev, uint32_t* counters_dev, int32_t asynchronous) {
   if (!start_ids_dev) return fail(GGNN_ERR_INVALID, "start_ids_dev is NULL");
   return query_impl(g, queries_dev, Q, k, beam, slack, pq_cap, visited_cap, max_iter, 0, start_ids_dev, n_start, stream,
-                    ids_dev, dists_dev, counters_dev, asynchronous);
+                    ids_dev, dists_dev, counters_dev, asynchronous, process_tuning());
 }
 
 int ggnn_query(const ggnn_graph* g, const void* queries_dev, int64_t Q, int32_t k, int32_t beam, float slack,
@@ -657,7 +721,9 @@ int ggnn_query_static(const ggnn_graph* g, const void* queries_dev, int64_t Q, i
   if (P > kWave || B > 2 * kWave)
     return fail(GGNN_ERR_LIMIT, "the two-launch search keeps its lists in registers: prioq <= 64 and best <= 128 (got %d, %d)", P, B);
   SearchParams sp;
-  int rc = make_search_params(B, P, V, it, slack, g->stats[1], &sp, true);
+  Tuning tune = process_tuning();
+  tune.cache_mode = 0;  // the lists live in registers here whatever the process-wide setting
+  int rc = make_search_params(B, P, V, it, slack, g->stats[1], &sp, tune, true);
   if (rc != GGNN_OK) return rc;
   const int slots = B <= kWave ? 1 : 2;
   const size_t need_lds = slots == 1 ? RegCache::lds_bytes(sp) : RegCache2::lds_bytes(sp);
