@@ -1,11 +1,17 @@
 #!/usr/bin/env python3
 """Benchmark of the GGNN hot path on one MI355X.
 
-Workload: the 1M x 128 configuration (float32 integer-valued vectors in [0,255] from a seeded
-1024-component Gaussian mixture, 10 000 queries of the same distribution, L2, K=24, k=10).
-The graph is built once on the GPU (build seconds are reported); a "step" is one search of the
-whole query batch at the operating point that first reaches Recall@10 >= 0.95.  Prints one
-JSON line.
+Workload of the timed region: the 1M x 128 configuration (float32 integer-valued vectors in [0,255] from a
+seeded 1024-component Gaussian mixture, 10 000 queries of the same distribution, L2, K=24, k=10).  The graph
+is built once on the GPU (build seconds are reported); a "step" is one search of the whole query batch at the
+operating point that first reaches Recall@10 >= 0.95.  Prints one JSON line.
+
+Beside the timed region the default run also records (each outside the timed region, each in a try block of
+its own so that a failure costs that record only): the QPS-vs-recall curve of the workload, the recall of the
+operating point on a fresh 100 000-query batch it was not tuned on, the for-all quality of the constructed
+graph, the same workload with four levels, and compact records (construction seconds, curve, roofline of the
+search kernel) of the other workloads: 1M x 96 real-valued with k = 10 and k = 100, 1.2M x 100 cosine with
+K = 40, and 10M x 128 uint8.  --quick skips them.
 """
 from __future__ import annotations
 
@@ -14,32 +20,45 @@ import json
 import os
 import sys
 import time
+import traceback
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+FORMULA = ("Q*(D*e + k*8) + pops*K*4 + rows_gathered*(4 + D*e), e = bytes per element; pops and rows_gathered are "
+           "counted by the kernel itself; rows actually gathered (start rows included) stand in for the method's "
+           "distance evaluations: a point proposed again after it was rejected counts as an evaluation of the method "
+           "but is not gathered again")
 
 
-def ground_truth(torch, base, queries, k, cosine=False, chunk=500):
+def ground_truth(torch, base, queries, k, cosine=False, chunk=500, base_chunk=4_000_000):
     """Exact k nearest neighbours by exhaustive search with torch (measurement plumbing, outside
     the timed region).  On integer-valued data every float32 partial sum is an exact integer."""
-    b, qs = base.float(), queries.float()
+    qs = queries.float()
     if cosine:
-        b = b / b.norm(dim=1, keepdim=True)
         qs = qs / qs.norm(dim=1, keepdim=True)
-    bn = (b * b).sum(1)
     ids, d = [], []
     for lo in range(0, qs.shape[0], chunk):
         q = qs[lo:lo + chunk]
-        if cosine:
-            dist = (1.0 - q @ b.T).clamp_min(0)
-        else:
-            dist = ((q * q).sum(1)[:, None] + bn[None, :] - 2.0 * (q @ b.T)).clamp_min(0).sqrt()
-        v, i = torch.topk(dist, k, dim=1, largest=False)
-        ids.append(i)
-        d.append(v)
+        best_v = best_i = None
+        for blo in range(0, base.shape[0], base_chunk):
+            b = base[blo:blo + base_chunk].float()
+            if cosine:
+                b = b / b.norm(dim=1, keepdim=True)
+                dist = (1.0 - q @ b.T).clamp_min(0)
+            else:
+                dist = ((q * q).sum(1)[:, None] + (b * b).sum(1)[None, :] - 2.0 * (q @ b.T)).clamp_min(0).sqrt()
+            v, i = torch.topk(dist, k, dim=1, largest=False)
+            i = i + blo
+            if best_v is None:
+                best_v, best_i = v, i
+            else:
+                v2, sel = torch.topk(torch.cat([best_v, v], 1), k, dim=1, largest=False)
+                best_v, best_i = v2, torch.gather(torch.cat([best_i, i], 1), 1, sel)
+        ids.append(best_i)
+        d.append(best_v)
     return torch.cat(ids), torch.cat(d)
 
 
@@ -49,6 +68,106 @@ def recall_at_k(dists, gt_d, rel=0.0):
     real-valued data, where the exhaustive search's float32 rounding differs from the library's)."""
     k = gt_d.shape[1]
     return float(((dists <= gt_d[:, k - 1:k] * (1.0 + rel)).sum(1).clamp(max=k).float().mean() / k).item())
+
+
+def algorithmic_bytes(cnt_sum, Q, D, esize, K, k):
+    """per launch: query vectors, one adjacency row per pop, one base row (and its id) per row gathered, results"""
+    return Q * (D * esize + k * 8) + cnt_sum[0] * K * 4 + cnt_sum[2] * (4 + D * esize)
+
+
+def time_point(torch, graph, queries, k, op, every, reps=3, out=None):
+    """One operating point: counters from one launch, then `reps` timed launches (HIP events on the launch
+    stream).  Returns (ids, dists, counter sums, ms per launch)."""
+    kw = dict(pq_cap=op.get("pq_cap", 64), visited_cap=op["visited_cap"], every_layer=every)
+    if out is None:
+        ids, dists, cnt = graph.query(queries, k, op["beam"], op["slack"], counters=True, **kw)
+    else:
+        ids, dists = out
+        _, _, cnt = graph.query(queries, k, op["beam"], op["slack"], counters=True, out=out, **kw)
+    stream = torch.cuda.current_stream()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(reps):
+        graph.query(queries, k, op["beam"], op["slack"], out=(ids, dists), asynchronous=True, **kw)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    return ids, dists, cnt.double().sum(0).tolist(), e0.elapsed_time(e1) / reps
+
+
+def curve_of(torch, graph, queries, k, ops, every, gt_d, rel, D, esize, K):
+    """QPS-vs-recall points, each with the algorithmic rate of its launch."""
+    Q = queries.shape[0]
+    pts = []
+    for op in ops:
+        ids, dists, cs, ms = time_point(torch, graph, queries, k, op, every)
+        gbps = algorithmic_bytes(cs, Q, D, esize, K, k) / (ms * 1e-3) / 1e9
+        pts.append(dict(beam=op["beam"], slack=op["slack"], visited_cap=op["visited_cap"],
+                        recall=round(recall_at_k(dists, gt_d, rel), 4), qps=round(Q / ms * 1e3), kernel_ms=round(ms, 3),
+                        pops=round(cs[0] / Q, 1), rows_gathered=round(cs[2] / Q, 1), algorithmic_GBps=round(gbps, 1),
+                        frac=round(gbps / HBM_PEAK_GBS, 4)))
+    return pts
+
+
+def best_point(points, bar=0.95):
+    ok = [p for p in points if p["recall"] >= bar]
+    return max(ok, key=lambda p: p["qps"]) if ok else None
+
+
+def profile_value(path, key, op_tag=None):
+    """A figure taken from a committed rocprofv3 summary under profiles/ (only valid for the operating point
+    the summary names)."""
+    if not os.path.exists(path):
+        return None
+    text = open(path).read()
+    if op_tag is not None and op_tag not in text:
+        return None
+    for line in text.splitlines():
+        if line.startswith(key + ":"):
+            return float(line.split(":")[1].split()[0])
+    return None
+
+
+def workload_records(torch, ggnn, ggnn_inputs, name, dev, label, levels, build_iter, variants, every, n=None, gpu_gen=False):
+    """Compact records of another workload, one per (k, operating points) variant on one constructed graph:
+    construction seconds and phases, QPS-vs-recall points with the roofline figure of each, and the fastest
+    point at Recall >= 0.95 if there is one."""
+    cfg = dict(ggnn_inputs.CONFIGS[name])
+    t0 = time.perf_counter()
+    if gpu_gen:
+        N = n or cfg["N"]
+        base = ggnn_inputs.gmm_int_torch(N, cfg["D"], cfg["components"], cfg["sigma"], cfg["data_seed"], cfg["data_seed"] + 1,
+                                         dev, cfg["dtype"])
+        queries = ggnn_inputs.gmm_int_torch(cfg["Q"], cfg["D"], cfg["components"], cfg["sigma"], cfg["data_seed"],
+                                            cfg["query_seed"], dev, cfg["dtype"])
+    else:
+        base_np, queries_np, cfg = ggnn_inputs.make(name, n=n)
+        base, queries = torch.from_numpy(base_np).to(dev), torch.from_numpy(queries_np).to(dev)
+    torch.cuda.synchronize()
+    gen_s = time.perf_counter() - t0
+    N, D = base.shape
+    esize, K = base.element_size(), cfg["K"]
+    cosine = cfg["metric"] == "cosine"
+    t0 = time.perf_counter()
+    graph = ggnn.build(base, K, levels, seed=42, metric=ggnn.COSINE if cosine else ggnn.L2, visited_cap=build_iter, max_iter=build_iter)
+    torch.cuda.synchronize()
+    build_s = time.perf_counter() - t0
+    phases = graph.times()
+    rel = 0.0 if cfg["kind"] == "gmm" else 2e-5
+    e_row = 4 if cosine else esize  # a cosine graph gathers rows of its float32 unit-length copy
+    recs = []
+    for k, ops in variants:
+        _, gt_d = ground_truth(torch, base, queries, k, cosine=cosine)
+        pts = curve_of(torch, graph, queries, k, ops, every, gt_d, rel, D, e_row, K)
+        recs.append({"workload": "%s: N=%d D=%d %s %s K=%d k=%d levels=%d Q=%d" % (label, N, D, cfg["dtype"], cfg["metric"], K, k,
+                                                                                 levels, queries.shape[0]),
+                     "data": "synthetic (%s generator, %.1f s)" % ("torch, on the GPU" if gpu_gen else "numpy", gen_s),
+                     "descent": "every layer (Alg. 4)" if every else "top layer, then bottom layer (Sec. 4.4)",
+                     "build_seconds": round(build_s, 3), "build_limit": build_iter,
+                     "build_phases_ms": {kk: round(v, 1) for kk, v in phases.items() if kk.endswith("_ms") and kk != "total_ms"},
+                     "recall_at": k, "curve": pts, "at_recall_0.95": best_point(pts)})
+    del graph, base, queries
+    torch.cuda.empty_cache()
+    return recs
 
 
 def main():
@@ -66,7 +185,8 @@ def main():
     ap.add_argument("--large-batch", type=int, default=100_000, help="also time a batch of this many queries (0 = skip)")
     ap.add_argument("--build-iter", type=int, default=192,
                     help="visited capacity = iteration limit per layer of the construction searches")
-    ap.add_argument("--sweep", action="store_true", help="also trace the QPS-vs-recall curve")
+    ap.add_argument("--quick", action="store_true", help="the timed region and its roofline only: no curve, no other workloads")
+    ap.add_argument("--no-other-workloads", action="store_true", help="skip the records of the other workloads")
     ap.add_argument("--direct-drop", action="store_true",
                     help="search the top layer and then the bottom layer only (Sec. 4.4) instead of every layer (Alg. 4)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -91,6 +211,7 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
+    t_start = time.perf_counter()
     base_np, queries_np, cfg = ggnn_inputs.make(args.workload, n=args.n)
     base = torch.from_numpy(base_np).to(dev)
     queries = torch.from_numpy(queries_np).to(dev)
@@ -98,6 +219,8 @@ def main():
     Q, k, K = queries.shape[0], cfg["k"], cfg["K"]
     esize = base.element_size()
     metric = ggnn.COSINE if cfg["metric"] == "cosine" else ggnn.L2
+    e_row = 4 if metric == ggnn.COSINE else esize
+    extras = not args.quick
 
     # ---- construction (timed once; the graph stays resident) ----
     torch.cuda.synchronize()
@@ -107,48 +230,31 @@ def main():
     build_s = time.perf_counter() - t0
     phases = graph.times()
 
-    # roofline of the construction's dominant kernel (merge_kernel): adjacency rows and base rows
-    # its searches read, plus the query row and the K results of every search, over the merge time
-    n_search = sum(graph.n[l] for l in range(graph.L))  # lower bound on the searches launched
-    merge_bytes = phases["merge_pops"] * K * 4 + phases["merge_rows"] * (4 + D * esize)
+    # the construction's dominant kernel (merge_kernel): adjacency rows and base rows its searches read over the
+    # merge time.  This is an algorithmic rate: rows served by the L2 count too, so it is not a fraction of the
+    # HBM peak; the HBM-side rate comes from hardware counters (profiles/), for the bottom-layer merge dispatch
+    merge_bytes = phases["merge_pops"] * K * 4 + phases["merge_rows"] * (4 + D * e_row)
+    pmc_path = os.path.join(ROOT, "profiles", "query_kernel_%s_pmc.txt" % args.workload)
+    build_tag = "build_point: %s levels=%d build_limit=%d" % (args.workload, args.levels, args.build_iter)
+    merge_hbm = profile_value(pmc_path, "merge_bottom_hbm_GBps", build_tag)
     build_roofline = {"kernel": "merge_kernel", "bound": "hbm", "unit": "GB/s", "peak": HBM_PEAK_GBS,
-                      "achieved": round(merge_bytes / (phases["merge_ms"] * 1e-3) / 1e9, 1),
-                      "frac": round(merge_bytes / (phases["merge_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                      "algorithmic_GBps": round(merge_bytes / (phases["merge_ms"] * 1e-3) / 1e9, 1),
+                      "hbm_GBps": merge_hbm, "frac_hbm": round(merge_hbm / HBM_PEAK_GBS, 4) if merge_hbm else None,
                       "pops": int(phases["merge_pops"]), "rows_gathered": int(phases["merge_rows"]),
-                      "note": "algorithmic bytes: rows served by the L2 count too, so the rate can exceed the HBM "
-                              "peak; HBM-side rates measured with counters are in profiles/"}
+                      "note": "algorithmic_GBps counts rows served by the L2 too (upper layers, rows shared by neighbouring "
+                              "searches), so it may exceed the HBM peak and is not a roofline fraction; hbm_GBps / frac_hbm: "
+                              "FETCH_SIZE + WRITE_SIZE of the bottom-layer merge dispatch over its duration (profiles/)"}
 
-    gt_ids, gt_d = ground_truth(torch, base, queries, k, cosine=(metric == ggnn.COSINE))
+    _, gt_d = ground_truth(torch, base, queries, k, cosine=(metric == ggnn.COSINE))
     rel = 0.0 if cfg["kind"] == "gmm" else 2e-5  # integer-valued rows have exact float32 distances
 
-    # ---- operating point (found with --sweep; the default is the cheapest one that reaches
-    # Recall@10 >= 0.95 on this workload) and, on request, the QPS-vs-recall curve ----
+    # ---- operating point (the cheapest point of the curve below that keeps Recall@10 half a point above 0.95)
     ids = torch.empty((Q, k), dtype=torch.int32, device=dev)
     dists = torch.empty((Q, k), dtype=torch.float32, device=dev)
     chosen = dict(beam=args.beam, slack=args.slack, visited_cap=args.visited_cap, pq_cap=args.pq_cap)
     every = not args.direct_drop
     kw = dict(pq_cap=chosen["pq_cap"], visited_cap=chosen["visited_cap"], every_layer=every)
-    curve = []
-    if args.sweep:
-        sweep = [dict(beam=10, slack=sl, visited_cap=v, pq_cap=64)
-                 for (sl, v) in [(0.02, 40), (0.03, 40), (0.04, 48), (0.044, 48), (0.048, 48), (0.05, 56), (0.05, 64),
-                                 (0.065, 96), (0.08, 128), (0.1, 192), (0.15, 384), (0.2, 512), (0.3, 1024)]]
-        for op in sweep:
-            okw = dict(pq_cap=op["pq_cap"], visited_cap=op["visited_cap"], every_layer=every)
-            _, _, c = graph.query(queries, k, op["beam"], op["slack"], counters=True, out=(ids, dists), **okw)
-            rec = recall_at_k(dists, gt_d, rel)
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(3):
-                graph.query(queries, k, op["beam"], op["slack"], out=(ids, dists), asynchronous=True, **okw)
-            e1.record()
-            torch.cuda.synchronize()
-            ms = e0.elapsed_time(e1) / 3
-            cm = c.double().mean(0).tolist()
-            curve.append(dict(op, recall=round(rec, 4), qps=round(Q / ms * 1e3), pops=round(cm[0], 1),
-                              dist_evals=round(cm[1], 1)))
     _, _, cnt = graph.query(queries, k, chosen["beam"], chosen["slack"], counters=True, out=(ids, dists), **kw)
-    chosen["cnt"] = cnt
 
     # ---- timed region: exactly `steps` searches of the whole batch ----
     stream = torch.cuda.current_stream()
@@ -168,43 +274,77 @@ def main():
     qps = Q / ms_per_step * 1e3
     final_recall = recall_at_k(dists, gt_d, rel)
 
-    # ---- steady state: a batch large enough to keep every CU busy (the paper's own batch-size
-    # study peaks near 95 000 queries), and the rate at which this GPU serves random row gathers
+    # ---- roofline of the search kernel: algorithmic bytes per launch / kernel time ----
+    cs = cnt.double().sum(0).tolist()
+    algo_bytes = algorithmic_bytes(cs, Q, D, e_row, K, k)
+    achieved = algo_bytes / (kernel_ms * 1e-3) / 1e9
+    op_tag = "operating_point: %s levels=%d beam=%d slack=%g visited_cap=%d pq_cap=%d Q=%d" % (
+        args.workload, args.levels, chosen["beam"], chosen["slack"], chosen["visited_cap"], chosen["pq_cap"], Q)
+    traffic = profile_value(pmc_path, "traffic_bytes_per_launch", op_tag)
+    traffic = int(traffic) if traffic else None
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "frac_hbm": round(traffic / (kernel_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) if traffic else None,
+                "kernel": "query_kernel", "kernel_ms": round(kernel_ms, 3), "algorithmic_bytes_per_launch": int(algo_bytes),
+                "formula": FORMULA}
+
+    errors = {}
+
+    def attempt(name, fn):
+        try:
+            return fn()
+        except Exception as exc:  # a failed side record must not cost the benchmark line
+            errors[name] = "%s: %s" % (type(exc).__name__, exc)
+            traceback.print_exc(file=sys.stderr)
+            return None
+
+    # ---- QPS-vs-recall curve of the workload (10 000 queries) ----
+    curve = []
+    if extras:
+        sweep = [dict(beam=10, slack=sl, visited_cap=v, pq_cap=64)
+                 for (sl, v) in [(0.02, 40), (0.03, 40), (0.04, 48), (0.044, 48), (0.048, 48), (0.05, 56), (0.05, 64),
+                                 (0.065, 96), (0.08, 128), (0.1, 192), (0.15, 384), (0.2, 512), (0.3, 1024)]]
+        curve = attempt("curve", lambda: curve_of(torch, graph, queries, k, sweep, every, gt_d, rel, D, e_row, K)) or []
+
+    # ---- steady state and held-out recall: a fresh batch large enough to keep every CU busy (the paper's own
+    # batch-size study peaks near 95 000 queries); the operating point was not tuned on these queries
     large = None
     if args.large_batch > 0 and cfg["kind"] == "gmm":
-        qn = ggnn_inputs.gmm_int(args.large_batch, D, cfg["components"], cfg["sigma"], cfg["data_seed"],
-                                 cfg["query_seed"] + 7, cfg["dtype"])
-        ql = torch.from_numpy(qn).to(dev)
-        lids, ld, lcnt = graph.query(ql, k, chosen["beam"], chosen["slack"], counters=True, **kw)
-        e0l, e1l = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0l.record(stream)
-        for _ in range(3):
-            graph.query(ql, k, chosen["beam"], chosen["slack"], out=(lids, ld), asynchronous=True, **kw)
-        e1l.record(stream)
-        torch.cuda.synchronize()
-        lms = e0l.elapsed_time(e1l) / 3
-        lc = lcnt.double().sum(0).tolist()
-        lbytes = len(qn) * (D * esize + k * 8) + lc[0] * K * 4 + lc[2] * (4 + D * esize)
-        large = {"queries": len(qn), "qps": round(len(qn) / lms * 1e3, 1), "kernel_ms": round(lms, 3),
-                 "achieved_GBps": round(lbytes / (lms * 1e-3) / 1e9, 1),
-                 "frac_of_hbm_peak": round(lbytes / (lms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                 "note": "two launches with the bottom-layer searches ordered by region (one part per XCD); algorithmic "
-                         "bytes: a good part of the gathered rows is served by the L2"}
-        del ql, lids, ld, lcnt
+        def large_batch():
+            qn = ggnn_inputs.gmm_int(args.large_batch, D, cfg["components"], cfg["sigma"], cfg["data_seed"],
+                                     cfg["query_seed"] + 7, cfg["dtype"])
+            ql = torch.from_numpy(qn).to(dev)
+            lids, ld, lcs, lms = time_point(torch, graph, ql, k, chosen, every)
+            lbytes = algorithmic_bytes(lcs, len(qn), D, e_row, K, k)
+            ltag = op_tag.replace("Q=%d" % Q, "Q=%d" % len(qn))
+            ltraffic = profile_value(pmc_path, "large_batch_traffic_bytes", ltag)
+            rec = {"queries": len(qn), "qps": round(len(qn) / lms * 1e3, 1), "kernel_ms": round(lms, 3),
+                   "algorithmic_GBps": round(lbytes / (lms * 1e-3) / 1e9, 1),
+                   "traffic": int(ltraffic) if ltraffic else None,
+                   "frac_hbm": round(ltraffic / (lms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) if ltraffic else None,
+                   "note": "two launches with the bottom-layer searches ordered by region (one part per XCD); algorithmic_GBps "
+                           "counts rows served by the L2 too and is not a fraction of the HBM peak"}
+            if extras:
+                _, lgt = ground_truth(torch, base, ql, k)
+                rec["heldout_recall_at_10"] = round(recall_at_k(ld, lgt, rel), 4)
+            return rec
+        large = attempt("large_batch", large_batch)
+
     gather_ceiling = None
     if D * esize <= 512 and metric == ggnn.L2:  # the probe reads rows of up to 512 bytes of the array as given
-        n_probe = 12_000_000
-        pids = torch.randint(0, N, (n_probe,), device=dev, dtype=torch.int32)
-        pout = ggnn.gather_probe(base, pids, 1200)
-        torch.cuda.synchronize()
-        e0g, e1g = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0g.record(stream)
-        for _ in range(3):
-            ggnn.gather_probe(base, pids, 1200, out=pout)
-        e1g.record(stream)
-        torch.cuda.synchronize()
-        gather_ceiling = round(n_probe * (D * esize + 4) / (e0g.elapsed_time(e1g) / 3 * 1e-3) / 1e9, 1)
-        del pids, pout
+        def ceiling():
+            n_probe = 12_000_000
+            pids = torch.randint(0, N, (n_probe,), device=dev, dtype=torch.int32)
+            pout = ggnn.gather_probe(base, pids, 1200)
+            torch.cuda.synchronize()
+            e0g, e1g = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0g.record(stream)
+            for _ in range(3):
+                ggnn.gather_probe(base, pids, 1200, out=pout)
+            e1g.record(stream)
+            torch.cuda.synchronize()
+            return round(n_probe * (D * esize + 4) / (e0g.elapsed_time(e1g) / 3 * 1e-3) / 1e9, 1)
+        gather_ceiling = attempt("gather_ceiling", ceiling)
 
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
@@ -214,28 +354,35 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    # ---- roofline of the search kernel: algorithmic bytes per launch / kernel time ----
-    # per query: the query vector, one adjacency row per pop, one base row (and its id) per row
-    # actually gathered (start points included), the k results (ids + distances)
-    cnt = chosen["cnt"].double().sum(0).tolist()
-    s = graph.s
-    algo_bytes = Q * (D * esize + k * 8) + cnt[0] * K * 4 + cnt[2] * (4 + D * esize)
-    achieved = algo_bytes / (kernel_ms * 1e-3) / 1e9
-    # HBM bytes per launch measured with rocprofv3 counters (see profiles/): only valid for the
-    # operating point they were taken at
-    traffic = None
-    op_tag = "operating_point: %s levels=%d beam=%d slack=%g visited_cap=%d pq_cap=%d Q=%d" % (
-        args.workload, args.levels, chosen["beam"], chosen["slack"], chosen["visited_cap"], chosen["pq_cap"], Q)
-    pmc_path = os.path.join(ROOT, "profiles", "query_kernel_%s_pmc.txt" % args.workload)
-    if os.path.exists(pmc_path):
-        text = open(pmc_path).read()
-        if op_tag in text:
-            for line in text.splitlines():
-                if line.startswith("traffic_bytes_per_launch:"):
-                    traffic = int(line.split(":")[1])
-    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic, "kernel": "query_kernel",
-                "kernel_ms": round(kernel_ms, 3), "algorithmic_bytes_per_launch": int(algo_bytes)}
+    # ---- for-all quality of the constructed bottom layer (Sec. 5.2.4): C@1 / C@10 of sampled rows
+    quality = None
+    if extras:
+        def graph_quality():
+            sample = torch.arange(0, N, max(1, N // 2000), device=dev)
+            gi, _ = ground_truth(torch, base, base[sample], 11, cosine=(metric == ggnn.COSINE))
+            e0_, _, _ = graph.export_layer(0)
+            rows = torch.from_numpy(e0_[sample.cpu().numpy()]).to(dev)
+            truth = gi[:, 1:11]  # the nearest is the point itself
+            c1 = (rows[:, 0:1] == truth[:, 0:1]).float().mean().item()
+            c10 = (rows[:, :12, None] == truth[:, None, :]).any(1).float().sum(1).div(10).mean().item()
+            return {"sample": int(sample.numel()), "c_at_1": round(c1, 4), "c_at_10": round(c10, 4),
+                    "note": "first entry / first 12 entries of a row against the exact 1 / 10 nearest neighbours"}
+        quality = attempt("graph_quality", graph_quality)
+
+    # ---- the same workload with four levels (the paper's own choice) ----
+    levels4 = None
+    if extras and args.levels != 4 and args.workload == "sift1m":
+        def four_levels():
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            g4 = ggnn.build(base, K, 4, seed=42, metric=metric, visited_cap=args.build_iter, max_iter=args.build_iter)
+            torch.cuda.synchronize()
+            b4 = time.perf_counter() - t0
+            ops = [dict(beam=b, slack=sl, visited_cap=v) for (b, sl, v) in
+                   [(10, 0.03, 40), (10, 0.04, 48), (10, 0.048, 48), (10, 0.05, 64), (16, 0.04, 64), (10, 0.065, 96), (10, 0.08, 128)]]
+            pts = curve_of(torch, g4, queries, k, ops, True, gt_d, rel, D, e_row, K)
+            return {"build_seconds": round(b4, 3), "layers": g4.n, "curve": pts, "at_recall_0.95": best_point(pts)}
+        levels4 = attempt("levels4", four_levels)
 
     # ---- CPU baseline: the oracle's search of the same graph on a sample of the queries ----
     cpu = None
@@ -298,6 +445,31 @@ def main():
                             "graph_identical_to_gpu": bool(same_graph),
                             "sample": "%d x %d points, K=%d, 3 levels, construction limit %d" % (
                                 small_np.shape[0], small_np.shape[1], scfg["K"], args.build_iter)}
+            del sg, sb, gg
+        del og
+
+    # ---- the other workloads (compact records; their numbers are not `value`) ----
+    workloads = []
+    if extras and not args.no_other_workloads and args.workload == "sift1m" and args.n is None:
+        graph_bytes, graph_s, graph_n = graph.graph_bytes, graph.s, graph.n
+        del graph
+        del base, queries
+        torch.cuda.empty_cache()
+        specs = [
+            ("deep1m", lambda: workload_records(torch, ggnn, ggnn_inputs, "deep1m", dev, "deep1m", 4, 384,
+                                                [(10, [dict(beam=10, slack=0.35, visited_cap=v) for v in (128, 256, 512, 768)]),
+                                                 (100, [dict(beam=100, slack=0.35, visited_cap=v) for v in (512, 1024)])], False)),
+            ("glove1m", lambda: workload_records(torch, ggnn, ggnn_inputs, "glove1m", dev, "glove1m", 4, 384,
+                                                 [(10, [dict(beam=10, slack=0.35, visited_cap=v) for v in (512, 2048)])], False)),
+            ("sift10m_u8", lambda: workload_records(torch, ggnn, ggnn_inputs, "sift100m_u8", dev, "10M-point subset of sift100m_u8", 4, 192,
+                                                    [(10, [dict(beam=10, slack=sl, visited_cap=v) for (sl, v) in
+                                                           ((0.05, 64), (0.08, 128), (0.12, 192), (0.2, 384))])], True,
+                                                    n=10_000_000, gpu_gen=True)),
+        ]
+        for nm, fn in specs:
+            workloads.extend(attempt(nm, fn) or [])
+    else:
+        graph_bytes, graph_s, graph_n = graph.graph_bytes, graph.s, graph.n
 
     out = {
         "metric": "queries/s at Recall@10>=0.95 (1M x 128 L2, k=10)", "value": round(qps, 1), "unit": "queries/s",
@@ -308,17 +480,23 @@ def main():
                    "beam": chosen["beam"], "slack": chosen["slack"], "pq_cap": chosen["pq_cap"],
                    "visited_cap": chosen["visited_cap"], "descent": "every layer (Alg. 4)" if every else "top layer, then bottom layer (Sec. 4.4)"},
         "recall_at_10": round(final_recall, 4),
+        "heldout_recall_at_10": (large or {}).get("heldout_recall_at_10"),
         "build_seconds": round(build_s, 3),
-        "build_config": {"levels": args.levels, "K": K, "segment_size": graph.s, "tau_build": 0.5, "refinements": 2,
+        "build_config": {"levels": args.levels, "K": K, "segment_size": graph_s, "tau_build": 0.5, "refinements": 2,
                          "pq_cap": 64, "visited_cap": args.build_iter, "max_iter": args.build_iter},
         "build_phases_ms": {kk: round(v, 2) for kk, v in phases.items() if kk.endswith("_ms")},
         "build_roofline": build_roofline,
-        "graph_bytes": graph.graph_bytes,
-        "pops_per_query": round(cnt[0] / Q, 1), "dist_evals_per_query": round(cnt[1] / Q, 1),
-        "rows_gathered_per_query": round(cnt[2] / Q, 1),
+        "graph_bytes": graph_bytes, "layers": graph_n,
+        "graph_quality": quality,
+        "pops_per_query": round(cs[0] / Q, 1), "dist_evals_per_query": round(cs[1] / Q, 1),
+        "rows_gathered_per_query": round(cs[2] / Q, 1),
         "large_batch": large,
         "random_row_gather_ceiling_GBps": gather_ceiling,
         "curve": curve,
+        "levels4": levels4,
+        "workloads": workloads,
+        "errors": errors or None,
+        "bench_seconds": round(time.perf_counter() - t_start, 1),
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
