@@ -212,9 +212,19 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     t_start = time.perf_counter()
-    base_np, queries_np, cfg = ggnn_inputs.make(args.workload, n=args.n)
-    base = torch.from_numpy(base_np).to(dev)
-    queries = torch.from_numpy(queries_np).to(dev)
+    cfg0 = ggnn_inputs.CONFIGS[args.workload]
+    if cfg0["dtype"] == "u8" and (args.n or cfg0["N"]) >= 2_000_000:
+        # too large to draw on the host in benchmark time: the same mixture drawn with torch on the GPU
+        cfg = dict(cfg0, N=args.n or cfg0["N"])
+        base = ggnn_inputs.gmm_int_torch(cfg["N"], cfg["D"], cfg["components"], cfg["sigma"], cfg["data_seed"],
+                                         cfg["data_seed"] + 1, dev, "u8")
+        queries = ggnn_inputs.gmm_int_torch(cfg["Q"], cfg["D"], cfg["components"], cfg["sigma"], cfg["data_seed"],
+                                            cfg["query_seed"], dev, "u8")
+        base_np = queries_np = None
+    else:
+        base_np, queries_np, cfg = ggnn_inputs.make(args.workload, n=args.n)
+        base = torch.from_numpy(base_np).to(dev)
+        queries = torch.from_numpy(queries_np).to(dev)
     N, D = base.shape
     Q, k, K = queries.shape[0], cfg["k"], cfg["K"]
     esize = base.element_size()
@@ -311,9 +321,14 @@ def main():
     large = None
     if args.large_batch > 0 and cfg["kind"] == "gmm":
         def large_batch():
-            qn = ggnn_inputs.gmm_int(args.large_batch, D, cfg["components"], cfg["sigma"], cfg["data_seed"],
-                                     cfg["query_seed"] + 7, cfg["dtype"])
-            ql = torch.from_numpy(qn).to(dev)
+            if base_np is None:
+                ql = ggnn_inputs.gmm_int_torch(args.large_batch, D, cfg["components"], cfg["sigma"], cfg["data_seed"],
+                                               cfg["query_seed"] + 7, dev, cfg["dtype"])
+                qn = ql
+            else:
+                qn = ggnn_inputs.gmm_int(args.large_batch, D, cfg["components"], cfg["sigma"], cfg["data_seed"],
+                                         cfg["query_seed"] + 7, cfg["dtype"])
+                ql = torch.from_numpy(qn).to(dev)
             lids, ld, lcs, lms = time_point(torch, graph, ql, k, chosen, every)
             lbytes = algorithmic_bytes(lcs, len(qn), D, e_row, K, k)
             ltag = op_tag.replace("Q=%d" % Q, "Q=%d" % len(qn))
@@ -388,6 +403,8 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import ggnn_ref as R
+        if base_np is None:
+            base_np, queries_np = base.cpu().numpy(), queries.cpu().numpy()
         og = R.Graph(base_np, K, args.levels, seed=42, metric=R.COSINE if metric == ggnn.COSINE else R.L2)
         for l in range(graph.L):
             e, tl, tb = graph.export_layer(l)
@@ -472,7 +489,7 @@ def main():
         graph_bytes, graph_s, graph_n = graph.graph_bytes, graph.s, graph.n
 
     out = {
-        "metric": "queries/s at Recall@10>=0.95 (1M x 128 L2, k=10)", "value": round(qps, 1), "unit": "queries/s",
+        "metric": "queries/s at Recall@10>=0.95 (1M x 128 L2, k=10)" if args.workload == "sift1m" and args.n is None else "queries/s (workload: see config)", "value": round(qps, 1), "unit": "queries/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32" if esize == 4 else "u8",
         "data": "synthetic",
