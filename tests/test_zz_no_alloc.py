@@ -36,4 +36,5 @@ def test_static_workspace_query_matches_query_ex_twice_in_a_row(sift10k):
         ggnn.query_static(g, big, 10, 10, 0.3, (torch.empty((200_000, 10), dtype=torch.int32, device="cuda"),
                                                  torch.empty((200_000, 10), dtype=torch.float32, device="cuda")))
     with pytest.raises(ggnn.GgnnError, match="registers"):
-        ggnn.query_static(g, q, 10, 10, 0.3, (ids, d), pq_cap=100)
+        ggnn.query_static(g, q, 10, 10, 0.3, (torch.empty((len(q), 10), dtype=torch.int32, device="cuda"),
+                                              torch.empty((len(q), 10), dtype=torch.float32, device="cuda")), pq_cap=100)
