@@ -238,7 +238,7 @@ int ggnn_set_cache_mode(int32_t mode);
  * more) are answered in two launches: the upper layers, then the bottom layer with the queries ordered
  * by the layer-1 point each arrived at, one contiguous part of that order per XCD, so that queries of
  * one region share an L2 cache.  Results and counters do not depend on it; the workspace comes from the
- * stream's memory pool (hipMallocAsync) and is returned to it.  Default 24576; 0 restores the default, a
+ * stream's memory pool (hipMallocAsync) and is returned to it.  Default 12288; 0 restores the default, a
  * value above every batch size turns the two-launch path off.  Process-wide default, as above. */
 int ggnn_set_split_threshold(int64_t min_queries);
 

@@ -74,7 +74,7 @@ struct Tuning {
   int32_t vis_min_iter;  // iteration limit from which visited moves to global memory; <= 0: never
   bool vis_forced;       // ... whatever the batch size
 };
-constexpr int64_t kSplitMinQueries = 24576;  // smaller batches gain nothing from the two-launch path
+constexpr int64_t kSplitMinQueries = 12288;  // smaller batches gain nothing from the two-launch path
 constexpr int32_t kVisGlobalMinIter = 1100;
 std::atomic<int> g_cache_mode{0};
 std::atomic<int64_t> g_split_min_queries{kSplitMinQueries};
