@@ -69,7 +69,8 @@ struct RegCacheT {
   // From this many keys per fetch on, prioq takes them all at once; fewer are inserted one by one.  (The
   // construction searches insert about 13 keys per fetch, user queries 2 - 3: with the threshold at 3 the
   // fixed cost of the joint insertion made user queries 2 - 10 % slower; at 8 the constructions are 1 - 5 %
-  // faster than with per-key counting and user queries unchanged.)
+  // faster than with per-key counting and user queries unchanged; at 16, or with one-by-one insertion
+  // only, the constructions are 3 % and 8 % slower.)
   static constexpr int kMultiInsertFrom = 8;
   // Hash slots (a power of two).  Up to 384 iterations: 1024 slots (4 KB, which six wavefronts per SIMD
   // can afford), filled to three eighths (or by the visited ids plus 128 rejected ids, if that is more):
