@@ -9,7 +9,8 @@ operating point that first reaches Recall@10 >= 0.95.  Prints one JSON line.
 Beside the timed region the default run also records (each outside the timed region, each in a try block of
 its own so that a failure costs that record only): the QPS-vs-recall curve of the workload, the recall of the
 operating point on a fresh 100 000-query batch it was not tuned on, the for-all quality of the constructed
-graph, the same workload with four levels, and compact records (construction seconds, curve, roofline of the
+graph, the same workload with four levels, what each construction step buys (refinement passes, the
+symmetric-linking constraint, the construction slack) with the batch-size series, and compact records (construction seconds, curve, roofline of the
 search kernel) of the other workloads: 1M x 96 real-valued with k = 10 and k = 100, 1.2M x 100 cosine with
 K = 40, and 10M x 128 uint8.  --quick skips them.
 """
@@ -399,6 +400,38 @@ def main():
             return {"build_seconds": round(b4, 3), "layers": g4.n, "curve": pts, "at_recall_0.95": best_point(pts)}
         levels4 = attempt("levels4", four_levels)
 
+    # ---- what each construction step buys (Sec. 4.2.1, Alg. 6, Eq. 4's slack) and the batch-size series, all at
+    # the timed operating point on this workload
+    ablations = None
+    if extras and args.workload == "sift1m":
+        def ablation_records():
+            def one(**kw):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                ga = ggnn.build(base, K, args.levels, seed=42, metric=metric, visited_cap=args.build_iter,
+                                max_iter=args.build_iter, **kw)
+                torch.cuda.synchronize()
+                secs = time.perf_counter() - t0
+                _, ad, acs, ams = time_point(torch, ga, queries, k, chosen, every)
+                rec = dict(kw, build_seconds=round(secs, 3), recall_at_10=round(recall_at_k(ad, gt_d, rel), 4),
+                           qps=round(Q / ams * 1e3, 1), pops_per_query=round(acs[0] / Q, 1),
+                           inverse_links_per_row=round(float(ga.export_inv_count(0).mean()), 3))
+                del ga
+                return rec
+            res = {"refinements": [one(refinements=r) for r in (0, 1, 2, 3)],
+                   "sym_constraint": [one(sym_constraint=on) for on in (True, False)],
+                   "tau_build": [one(tau_build=tb) for tb in (0.05, 0.1, 0.2, 0.5)]}
+            reps = -(-200_000 // Q)
+            big = queries.repeat(reps, 1)[torch.randperm(Q * reps, device=dev,
+                                                         generator=torch.Generator(device=dev).manual_seed(5))].contiguous()
+            series = []
+            for nq in (100, 1000, 3000, 10_000, 30_000, 100_000, 200_000):
+                _, _, _, bms = time_point(torch, graph, big[:nq].contiguous(), k, chosen, every)
+                series.append({"queries": nq, "kernel_ms": round(bms, 4), "qps": round(nq / bms * 1e3, 1)})
+            res["batch_size"] = series
+            return res
+        ablations = attempt("ablations", ablation_records)
+
     # ---- CPU baseline: the oracle's search of the same graph on a sample of the queries ----
     cpu = None
     if not args.no_cpu_baseline:
@@ -511,6 +544,7 @@ def main():
         "random_row_gather_ceiling_GBps": gather_ceiling,
         "curve": curve,
         "levels4": levels4,
+        "ablations": ablations,
         "workloads": workloads,
         "errors": errors or None,
         "bench_seconds": round(time.perf_counter() - t_start, 1),
