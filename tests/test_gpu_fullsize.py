@@ -191,7 +191,8 @@ def test_real_valued_workloads_at_full_size_sampled_parity(name, every):
 def test_uint8_workload_subset_sampled_parity():
     """A 4M-point subset of the 100M x 128 uint8 workload (generated on the GPU as the full set would be),
     four levels: integer distances from byte dot products, 24 rows in flight.  Sampled queries must equal
-    the oracle's search of the same graph bit for bit; reported distances are the exact ones."""
+    the oracle's search of the same graph bit for bit; reported distances are the exact ones; recall against the
+    oracle's exhaustive search, which the torch exhaustive search of the benchmark must reproduce."""
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
     import ggnn_inputs
@@ -227,3 +228,12 @@ def test_uint8_workload_subset_sampled_parity():
     assert np.array_equal(ids[sample], rids)
     assert np.array_equal(dists[sample].view(np.uint32), rd.view(np.uint32))
     assert np.array_equal(cnt[sample][:, :2].astype(np.uint32), rcnt)
+    # recall of the sampled queries by ids against the oracle's exhaustive search, and the exhaustive search
+    # that the benchmark uses on sets of this size against the oracle's distances
+    gt, gt_d = R.bruteforce(base, queries[sample], k)
+    rec = R.recall(ids[sample], gt)
+    assert rec >= 0.9, rec
+    from paper_1912_01059_amd.report import exhaustive, recall
+    _, td = exhaustive(torch, b, q, k)
+    assert np.allclose(td.cpu().numpy()[sample], gt_d, rtol=2e-6, atol=0)
+    assert abs(recall(torch.from_numpy(dists[sample]).to(dev), td[torch.from_numpy(sample).to(dev)], rel=0.0) - rec) <= 0.01
