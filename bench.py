@@ -215,7 +215,14 @@ def main():
     # ---- construction (timed once; the graph stays resident) ----
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    graph = ggnn.build(base, K, args.levels, seed=42, metric=metric, visited_cap=args.build_iter, max_iter=args.build_iter)
+    # a construction of minutes reports its steps on stderr (the callback waits for the stream after each step,
+    # which the short constructions are spared)
+    progress = None
+    if N >= 20_000_000:
+        def progress(step, l_top, l_m, seconds):
+            print("construction: %s(%d, %d) done at %.1f s" % (step, l_top, l_m, seconds), file=sys.stderr, flush=True)
+    graph = ggnn.build(base, K, args.levels, seed=42, metric=metric, visited_cap=args.build_iter, max_iter=args.build_iter,
+                       progress=progress)
     torch.cuda.synchronize()
     build_s = time.perf_counter() - t0
     phases = graph.times()

@@ -118,7 +118,18 @@ int ggnn_graph_create(const void* base_dev, int64_t N, int32_t D, int32_t K, int
 int ggnn_select(ggnn_graph* g, int32_t l_top);
 int ggnn_merge(ggnn_graph* g, int32_t l_top, int32_t l_m);
 int ggnn_sym(ggnn_graph* g, int32_t layer);
-int ggnn_build_steps(ggnn_graph* g); /* the sequence above on a created graph */
+int ggnn_build_steps(ggnn_graph* g); /* the sequence above on a created graph; frees the construction buffers
+                                       * when it is done (a later ggnn_sym allocates them again) */
+
+/* Progress of a long construction (minutes at 10^8 points).  `cb`, or NULL for none, is called by
+ * ggnn_build_steps on the calling thread after every step, once the step's work has completed on
+ * the graph's stream (so a construction with a callback waits for the stream after each step):
+ * step is "select", "merge" or "sym" (a string that lives as long as the library), l_top / l_m are
+ * the layers of the step (-1 where it has none), seconds the wall time since ggnn_build_steps began,
+ * user is handed through.  The callback must not call into the library with this graph.  Host
+ * pointers; the library keeps them until they are replaced or the graph is freed. */
+typedef void (*ggnn_progress_fn)(const char* step, int32_t l_top, int32_t l_m, double seconds, void* user);
+int ggnn_build_set_progress(ggnn_graph* g, ggnn_progress_fn cb, void* user);
 
 /* Times of the last ggnn_build* / ggnn_build_steps on this graph. */
 int ggnn_build_get_times(const ggnn_graph* g, ggnn_build_times* out);

@@ -48,9 +48,11 @@ class BuildTimes(C.Structure):
                 ("merge_rows", C.c_uint64), ("sym_pops", C.c_uint64), ("sym_rows", C.c_uint64)]
 
 
+ProgressFn = C.CFUNCTYPE(None, C.c_char_p, C.c_int32, C.c_int32, C.c_double, C.c_void_p)
+
 EXPORTS = [
     "ggnn_build", "ggnn_build_ex", "ggnn_graph_create", "ggnn_select", "ggnn_merge", "ggnn_sym",
-    "ggnn_build_steps", "ggnn_build_get_times", "ggnn_query", "ggnn_query_ex", "ggnn_query_with", "ggnn_query_static", "ggnn_query_from", "ggnn_graph_info",
+    "ggnn_build_steps", "ggnn_build_set_progress", "ggnn_build_get_times", "ggnn_query", "ggnn_query_ex", "ggnn_query_with", "ggnn_query_static", "ggnn_query_from", "ggnn_graph_info",
     "ggnn_graph_export", "ggnn_graph_import", "ggnn_graph_export_dnn", "ggnn_graph_import_dnn",
     "ggnn_graph_export_inv_count", "ggnn_set_cache_mode", "ggnn_set_split_threshold", "ggnn_set_global_visited_threshold", "ggnn_gather_probe", "ggnn_merge_shards", "ggnn_free", "ggnn_last_error",
 ]
@@ -72,6 +74,7 @@ def lib():
         L.ggnn_merge.argtypes = [vp, i32, i32]
         L.ggnn_sym.argtypes = [vp, i32]
         L.ggnn_build_steps.argtypes = [vp]
+        L.ggnn_build_set_progress.argtypes = [vp, ProgressFn, vp]
         L.ggnn_build_get_times.argtypes = [vp, C.POINTER(BuildTimes)]
         L.ggnn_query.argtypes = [vp, vp, i64, i32, i32, f32, vp, vp]
         L.ggnn_query_ex.argtypes = [vp, vp, i64, i32, i32, f32, i32, i32, i32, i32, vp, vp, vp, vp, i32]
@@ -256,6 +259,15 @@ class Graph:
         _check(lib().ggnn_build_steps(self.h))
         return self
 
+    def set_progress(self, fn):
+        """ggnn_build_set_progress: fn(step, l_top, l_m, seconds) after every step of build_steps, or None."""
+        if fn is None:
+            self._progress = None
+            _check(lib().ggnn_build_set_progress(self.h, C.cast(None, ProgressFn), None))
+            return
+        self._progress = ProgressFn(lambda step, l_top, l_m, seconds, user: fn(step.decode(), l_top, l_m, seconds))
+        _check(lib().ggnn_build_set_progress(self.h, self._progress, None))
+
     def times(self):
         t = BuildTimes()
         _check(lib().ggnn_build_get_times(self.h, C.byref(t)))
@@ -320,8 +332,18 @@ def graph_create(base, K, levels, seed=42, metric=L2, segment_size=0, tau_build=
 
 
 def build(base, K, levels, seed=42, metric=L2, segment_size=0, tau_build=0.0, refinements=2, pq_cap=0,
-          visited_cap=0, max_iter=0, sym_constraint=True, stream=None) -> Graph:
-    """ggnn_build_ex: the whole construction (Alg. 3 followed by r passes of Alg. 6)."""
+          visited_cap=0, max_iter=0, sym_constraint=True, stream=None, progress=None) -> Graph:
+    """ggnn_build_ex: the whole construction (Alg. 3 followed by r passes of Alg. 6).  With `progress`
+    (fn(step, l_top, l_m, seconds)): ggnn_graph_create, ggnn_build_set_progress, ggnn_build_steps."""
+    if progress is not None:
+        g = graph_create(base, K, levels, seed, metric, segment_size, tau_build, refinements, pq_cap, visited_cap,
+                         max_iter, sym_constraint, stream)
+        g.set_progress(progress)
+        try:
+            g.build_steps()
+        finally:
+            g.set_progress(None)
+        return g
     p = _params(base, metric, segment_size, tau_build, refinements, pq_cap, visited_cap, max_iter, sym_constraint, stream)
     h = C.c_void_p()
     _check(lib().ggnn_build_ex(_dev_ptr(base), base.shape[0], base.shape[1], K, levels, seed, C.byref(p), C.byref(h)))

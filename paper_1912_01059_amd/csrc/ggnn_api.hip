@@ -8,6 +8,7 @@
 #include <atomic>
 #include <mutex>
 #include <new>
+#include <chrono>
 #include <vector>
 
 #include "ggnn.h"
@@ -133,6 +134,8 @@ struct ggnn_graph {
   SymBuffers sb = {};
   bool sb_ready = false;
   ggnn_build_times times = {};
+  ggnn_progress_fn progress = nullptr;  // called by ggnn_build_steps after every step
+  void* progress_user = nullptr;
 };
 
 namespace {
@@ -570,23 +573,38 @@ int ggnn_sym(ggnn_graph* g, int32_t layer) {
   return GGNN_OK;
 }
 
+int ggnn_build_set_progress(ggnn_graph* g, ggnn_progress_fn cb, void* user) {
+  if (!g) return fail(GGNN_ERR_INVALID, "graph is NULL");
+  g->progress = cb;
+  g->progress_user = user;
+  return GGNN_OK;
+}
+
 int ggnn_build_steps(ggnn_graph* g) {
   if (!g) return fail(GGNN_ERR_INVALID, "graph is NULL");
   g->times = ggnn_build_times{};
   HIP_TRY(launch_fill_i32((int32_t*)g->work_dev, 16 * kWorkSlots, 0, g->stream));
   PhaseTimer total(g->stream);
+  const auto t0 = std::chrono::steady_clock::now();
+  // one step of the sequence, reported to the progress callback once its work is done
+  auto step = [&](const char* name, int l_top, int l_m, int rc) -> int {
+    if (rc != GGNN_OK || !g->progress) return rc;
+    if (hipStreamSynchronize(g->stream) != hipSuccess) return fail(GGNN_ERR_HIP, "hipStreamSynchronize failed after a construction step");
+    g->progress(name, l_top, l_m, std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count(), g->progress_user);
+    return GGNN_OK;
+  };
   int rc;
   for (int l_top = 0; l_top < g->L; l_top++) {
-    if (l_top > 0 && (rc = ggnn_select(g, l_top)) != GGNN_OK) return rc;
+    if (l_top > 0 && (rc = step("select", l_top, -1, ggnn_select(g, l_top))) != GGNN_OK) return rc;
     for (int l_m = l_top; l_m >= 0; l_m--) {
-      if ((rc = ggnn_merge(g, l_top, l_m)) != GGNN_OK) return rc;
-      if ((rc = ggnn_sym(g, l_m)) != GGNN_OK) return rc;
+      if ((rc = step("merge", l_top, l_m, ggnn_merge(g, l_top, l_m))) != GGNN_OK) return rc;
+      if ((rc = step("sym", -1, l_m, ggnn_sym(g, l_m))) != GGNN_OK) return rc;
     }
   }
   for (int r = 0; r < g->refinements; r++) {
     for (int l_m = g->L - 2; l_m >= 0; l_m--) {
-      if ((rc = ggnn_merge(g, g->L - 1, l_m)) != GGNN_OK) return rc;
-      if ((rc = ggnn_sym(g, l_m)) != GGNN_OK) return rc;
+      if ((rc = step("merge", g->L - 1, l_m, ggnn_merge(g, g->L - 1, l_m))) != GGNN_OK) return rc;
+      if ((rc = step("sym", -1, l_m, ggnn_sym(g, l_m))) != GGNN_OK) return rc;
     }
   }
   g->times.total_ms = total.stop();
@@ -596,6 +614,7 @@ int ggnn_build_steps(ggnn_graph* g) {
     g->times.merge_pops += w[8 * i + 0]; g->times.merge_rows += w[8 * i + 1];
     g->times.sym_pops += w[8 * i + 2]; g->times.sym_rows += w[8 * i + 3];
   }
+  release_sym_buffers(g);  // the construction buffers are not needed for queries
   return GGNN_OK;
 }
 
@@ -609,8 +628,6 @@ int ggnn_build_ex(const void* base_dev, int64_t N, int32_t D, int32_t K, int32_t
     *out = nullptr;
     return rc;
   }
-  // the construction buffers are not needed for queries
-  release_sym_buffers(*out);
   return GGNN_OK;
 }
 

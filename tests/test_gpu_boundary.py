@@ -94,3 +94,38 @@ def test_per_call_parameters_give_the_results_of_the_process_wide_ones(sift10k):
     a = g.query(q, 10, 16, 0.5, start_ids=starts)
     bq = g.query(q, 10, 16, 0.5, start_ids=starts, global_visited=1)
     assert torch.equal(a[0], bq[0]) and torch.equal(a[1].view(torch.int32), bq[1].view(torch.int32))
+
+
+def test_progress_callback_reports_every_step_of_the_construction(sift10k):
+    """ggnn_build_set_progress: the callback sees the steps of Alg. 3 (select, then merge and symmetric linking
+    from the new top layer down to the bottom) followed by the refinement passes of Alg. 6, in order, with
+    non-decreasing times; the graph is the one the plain construction gives, and a later step-wise call still
+    works after ggnn_build_steps has returned its construction buffers."""
+    _need_gpu()
+    import paper_1912_01059_amd as ggnn
+    base, queries, cfg = sift10k
+    b = torch.from_numpy(base).cuda()
+    L_, r = cfg["levels"], 2
+    seen = []
+    g = ggnn.build(b, cfg["K"], L_, seed=42, refinements=r, visited_cap=96, max_iter=96,
+                   progress=lambda step, l_top, l_m, seconds: seen.append((step, l_top, l_m, seconds)))
+    want = []
+    for l_top in range(L_):
+        if l_top > 0:
+            want.append(("select", l_top, -1))
+        for l_m in range(l_top, -1, -1):
+            want += [("merge", l_top, l_m), ("sym", -1, l_m)]
+    for _ in range(r):
+        for l_m in range(L_ - 2, -1, -1):
+            want += [("merge", L_ - 1, l_m), ("sym", -1, l_m)]
+    assert [s[:3] for s in seen] == want
+    times = [s[3] for s in seen]
+    assert all(t1 >= t0 >= 0.0 for t0, t1 in zip(times, times[1:]))
+    plain = ggnn.build(b, cfg["K"], L_, seed=42, refinements=r, visited_cap=96, max_iter=96)
+    for l in range(L_):
+        for x, y in zip(g.export_layer(l), plain.export_layer(l)):
+            assert (x is None and y is None) or np.array_equal(x, y)
+    assert g.times()["merge_pops"] == plain.times()["merge_pops"] > 0
+    n_seen = len(seen)
+    g.sym(0)  # allocates the construction buffers again; no callback outside ggnn_build_steps
+    assert len(seen) == n_seen
