@@ -391,11 +391,13 @@ def main():
     ablations = None
     if extras and args.workload == "sift1m":
         def ablation_records():
-            def one(**kw):
+            def one(limit=None, **kw):
+                lim = limit or args.build_iter
                 torch.cuda.synchronize()
                 t0 = time.perf_counter()
-                ga = ggnn.build(base, K, args.levels, seed=42, metric=metric, visited_cap=args.build_iter,
-                                max_iter=args.build_iter, **kw)
+                ga = ggnn.build(base, K, args.levels, seed=42, metric=metric, visited_cap=lim, max_iter=lim, **kw)
+                if limit:
+                    kw = dict(kw, build_limit=limit)
                 torch.cuda.synchronize()
                 secs = time.perf_counter() - t0
                 _, ad, acs, ams = time_point(torch, ga, queries, k, chosen, every)
@@ -406,7 +408,8 @@ def main():
                 return rec
             res = {"refinements": [one(refinements=r) for r in (0, 1, 2, 3)],
                    "sym_constraint": [one(sym_constraint=on) for on in (True, False)],
-                   "tau_build": [one(tau_build=tb) for tb in (0.05, 0.1, 0.2, 0.5)]}
+                   "tau_build": [one(tau_build=tb) for tb in (0.05, 0.1, 0.2, 0.5)],
+                   "build_limit": [one(limit=v) for v in (64, 96, 128, 192, 384)]}
             reps = -(-200_000 // Q)
             big = queries.repeat(reps, 1)[torch.randperm(Q * reps, device=dev,
                                                          generator=torch.Generator(device=dev).manual_seed(5))].contiguous()

@@ -17,7 +17,9 @@ constexpr int kPasses = GGNN_PASSES;  // 8 rows per pass: up to 8*kPasses rows i
 // Wavefronts per SIMD the register allocation of query_kernel and merge_kernel aims at: with rows of up
 // to 512 bytes six fit (80 registers; the user-query kernel then spills a few registers around
 // Transform, once per layer, not inside the search loop), and both are faster for the added residency.
-// The sym kernel would spill inside its loop and is left alone.
+// The sym kernel would spill inside its loop and is left alone.  (Eight per SIMD need 64 registers, one
+// gather pass in flight instead of two and a 512-slot table to fit LDS: measured, the 10 000-query batch of
+// 512-byte rows takes 0.93 ms instead of 0.73 ms; the smaller table alone costs 9 %.)
 template <int DT, int NCH>
 struct SearchWavesPerSimd {
   static constexpr int value = (Elem<DT>::lanes == kRowLanes && NCH <= 4) ? 6 : 1;
