@@ -69,3 +69,36 @@ def test_recall_counts_distances_within_the_kth(small):
     assert abs(report.recall(found, gt_d, rel=0.0) - (2 + 2) / 6) < 1e-6
     import bench
     assert abs(bench.recall_at_k(found, gt_d) - (2 + 2) / 6) < 1e-6
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_algorithmic_bytes_follow_the_stated_formula():
+    import bench
+    # 3 queries of 128 float32 elements, k = 10, K = 24: 7 pops and 50 rows gathered in all
+    want = 3 * (128 * 4 + 10 * 8) + 7 * 24 * 4 + 50 * (4 + 128 * 4)
+    assert bench.algorithmic_bytes([7, 60, 50, 0], 3, 128, 4, 24, 10) == want
+    assert "rows_gathered*(4 + D*e)" in bench.FORMULA and "pops*K*4" in bench.FORMULA
+
+
+def test_best_point_is_the_fastest_at_the_recall_bar():
+    import bench
+    pts = [dict(recall=0.94, qps=30), dict(recall=0.951, qps=20), dict(recall=0.97, qps=10)]
+    assert bench.best_point(pts)["qps"] == 20
+    assert bench.best_point(pts[:1]) is None
+
+
+def test_profile_figures_are_only_taken_for_the_operating_point_they_name(tmp_path):
+    import bench
+    p = tmp_path / "x.txt"
+    p.write_text("operating_point: Q=10000 slack=0.048\ntraffic_bytes_per_launch: 3520000000 bytes\n")
+    assert bench.profile_value(str(p), "traffic_bytes_per_launch", "operating_point: Q=10000 slack=0.048") == 3.52e9
+    assert bench.profile_value(str(p), "traffic_bytes_per_launch", "operating_point: Q=10000 slack=0.05") is None
+    assert bench.profile_value(str(tmp_path / "none.txt"), "traffic_bytes_per_launch") is None
