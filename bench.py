@@ -93,17 +93,17 @@ def best_point(points, bar=0.95):
     return max(ok, key=lambda p: p["qps"]) if ok else None
 
 
-def profile_value(path, key, op_tag=None):
-    """A figure taken from a committed rocprofv3 summary under profiles/ (only valid for the operating point
-    the summary names)."""
-    if not os.path.exists(path):
-        return None
-    text = open(path).read()
-    if op_tag is not None and op_tag not in text:
-        return None
-    for line in text.splitlines():
-        if line.startswith(key + ":"):
-            return float(line.split(":")[1].split()[0])
+def profile_value(key, op_tag):
+    """A figure taken from a committed rocprofv3 counter summary (profiles/*_pmc.txt): only from the summary
+    that names this workload, size and operating point in a line of its own (`op_tag`)."""
+    import glob
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*_pmc.txt"))):
+        text = open(path).read()
+        if op_tag not in text.splitlines():
+            continue
+        for line in text.splitlines():
+            if line.startswith(key + ":"):
+                return float(line.split(":")[1].split()[0])
     return None
 
 
@@ -231,9 +231,8 @@ def main():
     # merge time.  This is an algorithmic rate: rows served by the L2 count too, so it is not a fraction of the
     # HBM peak; the HBM-side rate comes from hardware counters (profiles/), for the bottom-layer merge dispatch
     merge_bytes = phases["merge_pops"] * K * 4 + phases["merge_rows"] * (4 + D * e_row)
-    pmc_path = os.path.join(ROOT, "profiles", "query_kernel_%s_pmc.txt" % args.workload)
-    build_tag = "build_point: %s levels=%d build_limit=%d" % (args.workload, args.levels, args.build_iter)
-    merge_hbm = profile_value(pmc_path, "merge_bottom_hbm_GBps", build_tag)
+    build_tag = "build_point: %s N=%d levels=%d build_limit=%d" % (args.workload, N, args.levels, args.build_iter)
+    merge_hbm = profile_value("merge_bottom_hbm_GBps", build_tag)
     build_roofline = {"kernel": "merge_kernel", "bound": "hbm", "unit": "GB/s", "peak": HBM_PEAK_GBS,
                       "algorithmic_GBps": round(merge_bytes / (phases["merge_ms"] * 1e-3) / 1e9, 1),
                       "hbm_GBps": merge_hbm, "frac_hbm": round(merge_hbm / HBM_PEAK_GBS, 4) if merge_hbm else None,
@@ -275,9 +274,9 @@ def main():
     cs = cnt.double().sum(0).tolist()
     algo_bytes = algorithmic_bytes(cs, Q, D, e_row, K, k)
     achieved = algo_bytes / (kernel_ms * 1e-3) / 1e9
-    op_tag = "operating_point: %s levels=%d beam=%d slack=%g visited_cap=%d pq_cap=%d Q=%d" % (
-        args.workload, args.levels, chosen["beam"], chosen["slack"], chosen["visited_cap"], chosen["pq_cap"], Q)
-    traffic = profile_value(pmc_path, "traffic_bytes_per_launch", op_tag)
+    op_tag = "operating_point: %s N=%d levels=%d beam=%d slack=%g visited_cap=%d pq_cap=%d Q=%d" % (
+        args.workload, N, args.levels, chosen["beam"], chosen["slack"], chosen["visited_cap"], chosen["pq_cap"], Q)
+    traffic = profile_value("traffic_bytes_per_launch", op_tag)
     traffic = int(traffic) if traffic else None
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
@@ -319,7 +318,7 @@ def main():
             lids, ld, lcs, lms = time_point(torch, graph, ql, k, chosen, every)
             lbytes = algorithmic_bytes(lcs, len(qn), D, e_row, K, k)
             ltag = op_tag.replace("Q=%d" % Q, "Q=%d" % len(qn))
-            ltraffic = profile_value(pmc_path, "large_batch_traffic_bytes", ltag)
+            ltraffic = profile_value("large_batch_traffic_bytes", ltag)
             rec = {"queries": len(qn), "qps": round(len(qn) / lms * 1e3, 1), "kernel_ms": round(lms, 3),
                    "algorithmic_GBps": round(lbytes / (lms * 1e-3) / 1e9, 1),
                    "traffic": int(ltraffic) if ltraffic else None,

@@ -95,10 +95,23 @@ def test_best_point_is_the_fastest_at_the_recall_bar():
     assert bench.best_point(pts[:1]) is None
 
 
-def test_profile_figures_are_only_taken_for_the_operating_point_they_name(tmp_path):
+def test_profile_figures_are_only_taken_for_the_operating_point_they_name(tmp_path, monkeypatch):
     import bench
-    p = tmp_path / "x.txt"
-    p.write_text("operating_point: Q=10000 slack=0.048\ntraffic_bytes_per_launch: 3520000000 bytes\n")
-    assert bench.profile_value(str(p), "traffic_bytes_per_launch", "operating_point: Q=10000 slack=0.048") == 3.52e9
-    assert bench.profile_value(str(p), "traffic_bytes_per_launch", "operating_point: Q=10000 slack=0.05") is None
-    assert bench.profile_value(str(tmp_path / "none.txt"), "traffic_bytes_per_launch") is None
+    (tmp_path / "profiles").mkdir()
+    (tmp_path / "profiles" / "a_pmc.txt").write_text("operating_point: w N=10 Q=10000 slack=0.048\ntraffic_bytes_per_launch: 3520000000 bytes\n")
+    (tmp_path / "profiles" / "b_pmc.txt").write_text("operating_point: w N=20 Q=10000 slack=0.048\ntraffic_bytes_per_launch: 99 bytes\n")
+    monkeypatch.setattr(bench, "ROOT", str(tmp_path))
+    assert bench.profile_value("traffic_bytes_per_launch", "operating_point: w N=10 Q=10000 slack=0.048") == 3.52e9
+    assert bench.profile_value("traffic_bytes_per_launch", "operating_point: w N=20 Q=10000 slack=0.048") == 99.0
+    assert bench.profile_value("traffic_bytes_per_launch", "operating_point: w N=10 Q=10000 slack=0.05") is None
+    assert bench.profile_value("traffic_bytes_per_launch", "operating_point: w N=1") is None  # whole lines only
+    assert bench.profile_value("no_such_key", "operating_point: w N=10 Q=10000 slack=0.048") is None
+
+
+def test_committed_counter_summaries_name_their_operating_points():
+    """The benchmark's own workload finds its HBM traffic figures in profiles/ (the tags are whole lines)."""
+    import bench
+    tag = "operating_point: sift1m N=1000000 levels=3 beam=10 slack=0.048 visited_cap=48 pq_cap=64 Q=10000"
+    assert bench.profile_value("traffic_bytes_per_launch", tag) > 1e9
+    assert bench.profile_value("large_batch_traffic_bytes", tag.replace("Q=10000", "Q=100000")) > 1e9
+    assert bench.profile_value("merge_bottom_hbm_GBps", "build_point: sift1m N=1000000 levels=3 build_limit=192") > 1000
