@@ -107,10 +107,12 @@ def profile_value(key, op_tag):
     return None
 
 
-def workload_records(torch, ggnn, ggnn_inputs, name, dev, label, levels, build_iter, variants, every, n=None, gpu_gen=False):
+def workload_records(torch, ggnn, ggnn_inputs, name, dev, label, levels, build_iter, variants, every, n=None, gpu_gen=False,
+                     large=0):
     """Compact records of another workload, one per (k, operating points) variant on one constructed graph:
     construction seconds and phases, QPS-vs-recall points with the roofline figure of each, and the fastest
-    point at Recall >= 0.95 if there is one."""
+    point at Recall >= 0.95 if there is one.  `large` (sets drawn on the GPU): that point again on a fresh batch
+    of so many queries, with its recall measured on the first 10 000 of them."""
     cfg = dict(ggnn_inputs.CONFIGS[name])
     t0 = time.perf_counter()
     if gpu_gen:
@@ -145,6 +147,21 @@ def workload_records(torch, ggnn, ggnn_inputs, name, dev, label, levels, build_i
                      "build_seconds": round(build_s, 3), "build_limit": build_iter,
                      "build_phases_ms": {kk: round(v, 1) for kk, v in phases.items() if kk.endswith("_ms") and kk != "total_ms"},
                      "recall_at": k, "curve": pts, "at_recall_0.95": best_point(pts)})
+        if large > 0 and gpu_gen and best_point(pts):
+            op = best_point(pts)
+            ql = ggnn_inputs.gmm_int_torch(large, cfg["D"], cfg["components"], cfg["sigma"], cfg["data_seed"],
+                                           cfg["query_seed"] + 7, dev, cfg["dtype"])
+            _, ld, lcs, lms = time_point(torch, graph, ql, k, op, every)
+            _, lgt = ground_truth(torch, base, ql[:10_000], k, cosine=cosine)
+            lbytes = algorithmic_bytes(lcs, large, D, e_row, K, k)
+            recs[-1]["large_batch"] = {"queries": large, "slack": op["slack"], "visited_cap": op["visited_cap"],
+                                       "qps": round(large / lms * 1e3, 1), "kernel_ms": round(lms, 3),
+                                       "algorithmic_GBps": round(lbytes / (lms * 1e-3) / 1e9, 1),
+                                       "frac": round(lbytes / (lms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                                       "heldout_recall": round(recall_at_k(ld[:10_000], lgt, rel), 4),
+                                       "note": "fresh queries, two launches with the bottom-layer searches ordered by region; "
+                                               "the algorithmic rate counts rows served by the L2 too"}
+            del ql
     del graph, base, queries
     torch.cuda.empty_cache()
     return recs
@@ -502,7 +519,7 @@ def main():
             ("sift10m_u8", lambda: workload_records(torch, ggnn, ggnn_inputs, "sift100m_u8", dev, "10M-point subset of sift100m_u8", 4, 192,
                                                     [(10, [dict(beam=10, slack=sl, visited_cap=v) for (sl, v) in
                                                            ((0.05, 64), (0.08, 128), (0.1, 160), (0.12, 192), (0.2, 384))])], True,
-                                                    n=10_000_000, gpu_gen=True)),
+                                                    n=10_000_000, gpu_gen=True, large=100_000)),
         ]
         for nm, fn in specs:
             workloads.extend(attempt(nm, fn) or [])
