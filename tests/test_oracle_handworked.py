@@ -118,6 +118,46 @@ def test_iteration_limit_cuts_the_search():
     assert (ids, d) == ([11], [1.0])
 
 
+def test_full_visited_list_forgets_its_oldest_entry():
+    """Alg. 2 Pop appends the popped point to a visited list of bounded size; once the list is full the entry
+    that has been there longest makes room (the library never lets this happen: it asks for an iteration limit
+    within the capacity; the oracle takes any pair).  The chain of the case above (id i at 12 - i, row [i+1,
+    i-1], start points id0 and id1, B = 1, tau = 0.5, d_nn = 10, prioq 4, query at 0), four iterations.
+    Capacity 1: visited holds the last popped point only.
+      start: best = 1(11), prioq = [1(11), 0(12)], thr = 11 + 5 = 16.                               evals 2
+      pop 1, visited [1]: 2(10) enters, 0 is in prioq.  best = 2, prioq = [2, 0], thr = 15.         evals 3
+      pop 2, visited [2]: 3(9) enters (thr = 13.5); 1 is in no list any more: evaluated, 11 <= 13.5,
+        enters prioq = [3(9), 1(11), 0(12)] and falls off best again.                               evals 5
+      pop 3, visited [3]: 4(8) enters (thr = 12); 2(10) evaluated again, enters prioq = [4, 2, 1, 0].  evals 7
+      pop 4, visited [4]: 5(7) enters (thr = 10.5), prioq = [5, 2, 1, 0]; 3(9) evaluated again, enters:
+        prioq = [5, 3, 2, 1].                                                                       evals 9
+    Result id5 at 7 after 4 pops and 9 evaluations (6 with room for every popped point).  A list that stops
+    taking entries when it is full would keep 1 for good: the second pop evaluates 3 only, the third and the
+    fourth two points each: 8 evaluations."""
+    xs = [12 - i for i in range(12)]
+    rows = [[1, 2]] + [[i + 1, i - 1] for i in range(1, 11)] + [[10, 9]]
+    g, _ = _line_graph(xs, rows, K=2, s=2, L=2, mean=1.0, mx=10.0, upper=[([0, 1], [0, 1], None)])
+    assert _query(g, 0.0, 1, 1, 0.5, pq_cap=4, visited_cap=1, max_iter=4) == ([5], [7.0], [4, 9])
+    assert _query(g, 0.0, 1, 1, 0.5, pq_cap=4, visited_cap=4, max_iter=4) == ([5], [7.0], [4, 6])
+
+
+def test_visited_list_is_overwritten_in_order_of_arrival():
+    """The same chain with capacity 2, the row of id3 changed to [4, 0] and that of id4 to [5, 1]: the list
+    runs [1], [1, 2], then 3 takes the place of 1 (the oldest), then 4 the place of 2.
+      start 2 evaluations; pop 1: 2 enters (3), 0 is in prioq; pop 2: 3 enters (4), 1 visited;
+      pop 3, visited {3, 2}: 4(8) enters (5), thr = 12, 0(12) is still in prioq;
+      pop 4, visited {3, 4}: 5(7) enters (6), thr = 10.5; 1 is neither listed nor visited any more: evaluated
+      (7) and rejected (11 > 10.5).
+    4 pops, 7 evaluations.  Overwriting the newest entry instead would leave {1, 4}, never overwriting {1, 2}:
+    either way 1 is still known at the fourth pop and the count is 6."""
+    xs = [12 - i for i in range(12)]
+    rows = [[1, 2]] + [[i + 1, i - 1] for i in range(1, 11)] + [[10, 9]]
+    rows[3] = [4, 0]
+    rows[4] = [5, 1]
+    g, _ = _line_graph(xs, rows, K=2, s=2, L=2, mean=1.0, mx=10.0, upper=[([0, 1], [0, 1], None)])
+    assert _query(g, 0.0, 1, 1, 0.5, pq_cap=4, visited_cap=2, max_iter=4) == ([5], [7.0], [4, 7])
+
+
 def test_full_prioq_drops_its_largest_entry():
     """Alg. 2 Push into a prioq of one entry on a sparse graph: a=id0 at 5 and b=id1 at 4 are the start
     points, t=id2 at 1 is known to a only, u=id3 at 6; a-[t,b], b-[u,a], t-[a,b], u-[b,a]; B = 2, tau = 0.5,

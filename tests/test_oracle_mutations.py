@@ -89,6 +89,11 @@ MUTATIONS = [
      "path_inside_the_sphere"),
     ("granted_links_not_written_into_the_rows", "    for (int i = 0; i < nl; i++) row[o++] = links[i];\n", "",
      "path_inside_the_sphere or shifted_midpoint"),
+    ("visited_list_stops_taking_entries_when_full",
+     "    c->vis[c->vhead] = id;\n    c->vhead = (c->vhead + 1) % c->V;\n    if (c->nv < c->V) c->nv++;\n",
+     "    if (c->nv < c->V) c->vis[c->nv++] = id;\n", "full_visited_list_forgets"),
+    ("visited_list_overwrites_its_newest_entry", "    c->vhead = (c->vhead + 1) % c->V;\n",
+     "    c->vhead = (c->vhead + 1 < c->V) ? c->vhead + 1 : c->V - 1;\n", "overwritten_in_order_of_arrival"),
 ]
 
 
