@@ -23,61 +23,78 @@ MAX_BLOCK_ELEMS = 1 << 28  # elements of one distance block: torch's float32 mat
 
 def exhaustive(torch, base, queries, k, cosine=False, chunk=500, check=8):
     """Exact k nearest neighbours by exhaustive search with torch: measurement plumbing, not part of the
-    library.  Works block by block over the queries and the base rows (MAX_BLOCK_ELEMS), then checks itself:
-    the distance of every reported neighbour is recomputed element by element from the two rows, and for
+    library.  Works block by block over the queries and the base rows (MAX_BLOCK_ELEMS) and checks itself:
+    the distance of every reported neighbour is recomputed element by element from the two rows (a block of
+    queries that fails this is searched again without a matrix product, with a warning on stderr), and for
     `check` queries spread over the batch the k-th distance is compared with a scan of all base rows that uses
-    no matrix product.  Raises RuntimeError if either check fails.  Returns (ids, distances)."""
+    no matrix product.  Raises RuntimeError if a check still fails at the end.  Returns (ids, distances)."""
+    import sys
     qs = queries.float()
     if cosine:
         qs = qs / qs.norm(dim=1, keepdim=True)
     n = base.shape[0]
     base_chunk = max(1, MAX_BLOCK_ELEMS // max(1, min(chunk, qs.shape[0])))
+    tol = 2e-4 if cosine else 1e-4
 
     def rows(lo, hi):
         b = base[lo:hi].float()
         return b / b.norm(dim=1, keepdim=True) if cosine else b
 
-    ids, d = [], []
-    for lo in range(0, qs.shape[0], chunk):
-        q = qs[lo:lo + chunk]
-        best_v = best_i = None
-        for blo in range(0, n, base_chunk):
-            b = rows(blo, blo + base_chunk)
-            if cosine:
+    def merge_topk(best, v, i):
+        if best is None:
+            return v, i
+        v2, sel = torch.topk(torch.cat([best[0], v], 1), k, dim=1, largest=False)
+        return v2, torch.gather(torch.cat([best[1], i], 1), 1, sel)
+
+    def search(q, with_product):
+        best = None
+        step = base_chunk if with_product else max(1, (1 << 26) // max(1, q.shape[0] * q.shape[1]))
+        for blo in range(0, n, step):
+            b = rows(blo, blo + step)
+            if not with_product:  # differences (or products) element by element, summed in float64
+                dist = ((1.0 - (q[:, None, :].double() * b[None, :, :].double()).sum(2)).clamp_min(0) if cosine
+                        else (q[:, None, :].double() - b[None, :, :].double()).pow(2).sum(2).sqrt()).float()
+            elif cosine:
                 dist = (1.0 - q @ b.T).clamp_min(0)
             else:
                 dist = ((q * q).sum(1)[:, None] + (b * b).sum(1)[None, :] - 2.0 * (q @ b.T)).clamp_min(0).sqrt()
             v, i = torch.topk(dist, min(k, b.shape[0]), dim=1, largest=False)
-            i = i + blo
-            if best_v is None:
-                best_v, best_i = v, i
-            else:
-                v2, sel = torch.topk(torch.cat([best_v, v], 1), k, dim=1, largest=False)
-                best_v, best_i = v2, torch.gather(torch.cat([best_i, i], 1), 1, sel)
-        ids.append(best_i)
-        d.append(best_v)
-    ids, d = torch.cat(ids), torch.cat(d)
+            best = merge_topk(best, v, i + blo)
+        return best
 
-    # every reported distance again, from the two rows alone
-    tol = 2e-4 if cosine else 1e-4
-    for lo in range(0, qs.shape[0], 4096):
-        q = qs[lo:lo + 4096].double()
-        nb = base[ids[lo:lo + 4096].reshape(-1)].double().reshape(q.shape[0], ids.shape[1], -1)
+    def recompute(q, ii):  # the reported neighbours' distances from the two rows alone, in float64
+        nb = base[ii.reshape(-1)].double().reshape(q.shape[0], ii.shape[1], -1)
         if cosine:
             nb = nb / nb.norm(dim=2, keepdim=True)
-            again = (1.0 - (nb * q[:, None, :]).sum(2)).clamp_min(0)
-        else:
-            again = (nb - q[:, None, :]).pow(2).sum(2).sqrt()
-        err = (again - d[lo:lo + 4096].double()).abs()
-        if bool((err > tol * (1.0 + again)).any()):
-            raise RuntimeError("exhaustive search: a reported distance differs from its recomputation by %g" % float(err.max()))
+            return (1.0 - (nb * q.double()[:, None, :]).sum(2)).clamp_min(0)
+        return (nb - q.double()[:, None, :]).pow(2).sum(2).sqrt()
+
+    def wrong(q, v, ii):
+        again = recompute(q, ii)
+        return bool(((again - v.double()).abs() > tol * (1.0 + again)).any())
+
+    ids, d = [], []
+    for lo in range(0, qs.shape[0], chunk):
+        q = qs[lo:lo + chunk]
+        v, ii = search(q, True)
+        if wrong(q, v, ii):
+            print("exhaustive search: the matrix product gave wrong distances for queries %d..%d; searching them "
+                  "again without it" % (lo, lo + q.shape[0] - 1), file=sys.stderr, flush=True)
+            v, ii = search(q, False)
+            if wrong(q, v, ii):
+                raise RuntimeError("exhaustive search: reported distances of queries %d..%d differ from their "
+                                   "recomputation" % (lo, lo + q.shape[0] - 1))
+        ids.append(ii)
+        d.append(v)
+    ids, d = torch.cat(ids), torch.cat(d)
+
     # the k-th distance of a few queries against a scan without a matrix product
     for r in sorted({int(x) for x in torch.linspace(0, qs.shape[0] - 1, min(check, qs.shape[0])).tolist()}):
         q = qs[r].double()
         kth = []
         for blo in range(0, n, 1_000_000):
             b = rows(blo, blo + 1_000_000).double()
-            dd = (1.0 - b @ q).clamp_min(0) if cosine else (b - q[None, :]).pow(2).sum(1).sqrt()
+            dd = (1.0 - (b * q[None, :]).sum(1)).clamp_min(0) if cosine else (b - q[None, :]).pow(2).sum(1).sqrt()
             kth.append(torch.topk(dd, min(k, dd.shape[0]), largest=False).values)
         want = torch.topk(torch.cat(kth), k, largest=False).values[k - 1]
         if abs(float(want) - float(d[r, k - 1])) > tol * (1.0 + float(want)):

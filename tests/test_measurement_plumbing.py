@@ -1,6 +1,6 @@
 """The exhaustive search behind every recall figure (`exhaustive` in the package's report module, which
-bench.py calls) against the oracle's plain definition, on the CPU; its two self-checks must fire when the
-matrix product it relies on returns wrong rows (as a float32 product with an output beyond 2 GiB has done on
+bench.py calls) against the oracle's plain definition, on the CPU; its two self-checks must act when the
+matrix product it relies on returns wrong values (as a float32 product with an output beyond 2 GiB has done on
 the GPU), and the recall measure must count what it says."""
 import numpy as np
 import pytest
@@ -47,7 +47,10 @@ def test_blocks_stay_under_the_limit(small, monkeypatch):
     assert np.allclose(d.numpy(), gt_d, rtol=2e-5, atol=2e-6)
 
 
-def test_self_checks_catch_a_wrong_product(small, monkeypatch):
+def test_wrong_rows_of_the_product_are_searched_again_without_it(small, monkeypatch, capfd):
+    """Rows of the product that are far too large (their distances clamp to zero, as seen on the GPU): the
+    recomputation of the reported distances notices, the block is searched again without a product, and the
+    result is still the oracle's."""
     base, queries = small
     real = torch.Tensor.__matmul__
 
@@ -55,11 +58,32 @@ def test_self_checks_catch_a_wrong_product(small, monkeypatch):
         out = real(a, b)
         if out.dtype == torch.float32 and out.dim() == 2 and out.shape[0] >= 8:
             out = out.clone()
-            out[out.shape[0] * 3 // 4:] = 1e9  # far too large a product: distances clamp to zero
+            out[out.shape[0] * 3 // 4:] = 1e9
         return out
 
     monkeypatch.setattr(torch.Tensor, "__matmul__", broken)
-    with pytest.raises(RuntimeError, match="exhaustive search"):
+    ids, d = report.exhaustive(torch, torch.from_numpy(base), torch.from_numpy(queries), 10, chunk=16)
+    monkeypatch.undo()
+    assert "searching them again without it" in capfd.readouterr().err
+    _, gt_d = R.bruteforce(base, queries, 10)
+    assert np.allclose(d.numpy(), gt_d, rtol=2e-5, atol=2e-6)
+
+
+def test_neighbours_hidden_by_the_product_are_caught_by_the_plain_scan(small, monkeypatch):
+    """Columns of the product that are far too small make half of the base points look far away: every reported
+    distance is right, but true neighbours are missing.  The scan without a product over a few queries raises."""
+    base, queries = small
+    real = torch.Tensor.__matmul__
+
+    def broken(a, b):
+        out = real(a, b)
+        if out.dtype == torch.float32 and out.dim() == 2 and out.shape[1] >= 64:
+            out = out.clone()
+            out[:, ::2] = -1e9
+        return out
+
+    monkeypatch.setattr(torch.Tensor, "__matmul__", broken)
+    with pytest.raises(RuntimeError, match="plain scan"):
         report.exhaustive(torch, torch.from_numpy(base), torch.from_numpy(queries), 10, chunk=16)
 
 
