@@ -258,7 +258,13 @@ def main():
                               "searches), so it may exceed the HBM peak and is not a roofline fraction; hbm_GBps / frac_hbm: "
                               "FETCH_SIZE + WRITE_SIZE of the bottom-layer merge dispatch over its duration (profiles/)"}
 
-    _, gt_d = ground_truth(torch, base, queries, k, cosine=(metric == ggnn.COSINE))
+    errors = {}
+    try:
+        _, gt_d = ground_truth(torch, base, queries, k, cosine=(metric == ggnn.COSINE))
+    except Exception as exc:  # no recall figure then, but the timed region and its roofline are still reported
+        gt_d = None
+        errors["ground_truth"] = "%s: %s" % (type(exc).__name__, exc)
+        traceback.print_exc(file=sys.stderr)
     rel = 0.0 if cfg["kind"] == "gmm" else 2e-5  # integer-valued rows have exact float32 distances
 
     # ---- operating point (the cheapest point of the curve below that keeps Recall@10 half a point above 0.95)
@@ -285,7 +291,7 @@ def main():
     kernel_ms = e0.elapsed_time(e1) / args.steps
     ms_per_step = wall_ms / args.steps
     qps = Q / ms_per_step * 1e3
-    final_recall = recall_at_k(dists, gt_d, rel)
+    final_recall = recall_at_k(dists, gt_d, rel) if gt_d is not None else None
 
     # ---- roofline of the search kernel: algorithmic bytes per launch / kernel time ----
     cs = cnt.double().sum(0).tolist()
@@ -300,8 +306,6 @@ def main():
                 "frac_hbm": round(traffic / (kernel_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) if traffic else None,
                 "kernel": "query_kernel", "kernel_ms": round(kernel_ms, 3), "algorithmic_bytes_per_launch": int(algo_bytes),
                 "formula": FORMULA}
-
-    errors = {}
 
     def attempt(name, fn):
         try:
@@ -460,7 +464,7 @@ def main():
         same = bool(np.array_equal(rids, ids[:ns].cpu().numpy()) and np.array_equal(rd, dists[:ns].cpu().numpy()))
         # the exhaustive search used for the recall figure, checked against the oracle's on a few queries
         _, bf_d = R.bruteforce(base_np, queries_np[:16], k, metric=R.COSINE if metric == ggnn.COSINE else R.L2)
-        gt_ok = bool(np.allclose(bf_d, gt_d[:16].cpu().numpy(), rtol=2e-5, atol=1e-6))
+        gt_ok = bool(np.allclose(bf_d, gt_d[:16].cpu().numpy(), rtol=2e-5, atol=1e-6)) if gt_d is not None else None
         cores = R.lib().ggnn_ref_num_threads()
         cpu = {"value": round(ns / cpu_s, 1), "unit": "queries/s", "cores": cores,
                "kind": "oracle", "sample": "first %d of the %d queries, same graph and operating point" % (ns, Q),
@@ -534,7 +538,7 @@ def main():
         "config": {"workload": "%s: N=%d D=%d Q=%d K=%d k=%d levels=%d" % (args.workload, N, D, Q, K, k, args.levels),
                    "beam": chosen["beam"], "slack": chosen["slack"], "pq_cap": chosen["pq_cap"],
                    "visited_cap": chosen["visited_cap"], "descent": "every layer (Alg. 4)" if every else "top layer, then bottom layer (Sec. 4.4)"},
-        "recall_at_10": round(final_recall, 4),
+        "recall_at_10": round(final_recall, 4) if final_recall is not None else None,
         "heldout_recall_at_10": (large or {}).get("heldout_recall_at_10"),
         "build_seconds": round(build_s, 3),
         "build_config": {"levels": args.levels, "K": K, "segment_size": graph_s, "tau_build": 0.5, "refinements": 2,
